@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the CodedReduce hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
+host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> cr_gd_update.
+Prints ONE JSON line: iterations/s, the roofline of the dominant kernel (measured live with HIP events on the
+library's stream) and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E bandwidth
+KERNEL_NAMES = ["partial_grads", "reduce_pieces", "encode", "decode", "update"]
+DESCRIPTIONS = {
+    "cfg1": "CR tree L=2 n=3 s=1, linear regression fp32, m=1200 d=100",
+    "cfg2": "CR tree L=2 n=4 s=1 (20 workers), linear regression fp32, m=100000 d=10000, GD lr=1e-6, random mask per step",
+    "cfg3": "CR tree L=3 n=4 s=1 (84 workers), logistic regression fp32, m=252000 d=4096, random mask per step",
+    "cfg4": "aggregation only: CR tree L=2 n=8 s=2 (72 workers), 248 fp32 partition-gradient vectors of length 2^24, encode+decode",
+    "cfg5": "CR tree L=3 n=6 s=2 (258 workers), linear regression, X bf16 / fp32 accumulate, m=2064000 d=1024, random mask per step",
+}
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def load_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (None if not measured)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        table = json.load(f)
+    entry = table.get(workload)
+    return None if entry is None else entry.get("bytes_per_launch")
+
+
+def cpu_baseline(cfg, data, plan_B, w_host, mask, g_gpu, budget_s: float):
+    """The oracle as it stands: the CR tree literally (every holder visits its own rows) in fp64 on the host cores."""
+    from oracle import cr_tree, gc_code, native
+
+    L, n, s = cfg["L"], cfg["n"], cfg["s"]
+    B = gc_code.search_encoding_matrix(n, s, 190201981)[0]
+    own, _ = cr_tree.cr_allocate(L, n, s, cfg["m"], B)
+    slabs = cr_tree.slabs_of(own)
+    visits = sum(e - b for _, b, e, _ in slabs)
+    native.num_threads()
+    t0 = time.perf_counter()
+    done_rows = 0
+    node_grads = [np.zeros(cfg["d"]) for _ in own]
+    complete = True
+    for k, (node, b, e, c) in enumerate(slabs):
+        node_grads[node] += float(c) * native.segment_gradient(data["X"], data["y"], w_host, b, e, cfg["model"])
+        done_rows += e - b
+        if time.perf_counter() - t0 > budget_s and k + 1 < len(slabs):
+            complete = False
+            break
+    parity = None
+    if complete:
+        rows = {}
+        _, g = cr_tree.cr_execute(L, n, s, node_grads, mask, lambda T: rows.setdefault(T, gc_code.decoding_row(B, T)))
+        parity = float(np.linalg.norm(g_gpu - g) / np.linalg.norm(g))
+    elapsed = time.perf_counter() - t0
+    its = (done_rows / visits) / elapsed
+    sample = (f"one whole CR iteration ({visits} row visits, all {len(slabs)} slabs, tree execute included)" if complete else
+              f"first {k + 1} of {len(slabs)} slabs ({done_rows} of {visits} row visits), scaled to one iteration")
+    return {"value": its, "unit": "iterations/s", "cores": native.num_threads(), "kind": "oracle", "sample": sample,
+            "seconds": elapsed}, parity
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle work for the CPU baseline (0 = skip)")
+    ap.add_argument("--teams", type=int, default=0, help="override the stage-1 work split")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_1902_01981_amd as cr
+    from cr_inputs import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    cr.load_library()
+    cfg = wl.config(args.workload)
+    L, n, s, m, d = cfg["L"], cfg["n"], cfg["s"], cfg["m"], cfg["d"]
+    aggregate = cfg["model"] == wl.AGGREGATE_ONLY
+    t0 = time.perf_counter()
+    plan = cr.cr_plan_ex(L, n, s, m, d, model=cfg["model"], x_dtype=cfg["x_dtype"])
+    if args.teams and not aggregate:
+        cr.cr_plan_set_teams(plan, args.teams)
+
+    # ---- inputs, generated on the host from the seed and moved to HBM before any timing
+    data = None
+    if aggregate:
+        node, rb, re_, coef = cr.cr_plan_get_slabs(plan)
+        cuts, member = wl.atoms_of(rb, re_)
+        atoms_dev = torch.empty((len(cuts) - 1, d), dtype=torch.float32, device="cuda")
+        step_cols = 1 << 22
+        for lo in range(0, d, step_cols):
+            hi = min(d, lo + step_cols)
+            atoms_dev[:, lo:hi] = torch.from_numpy(wl.atom_vectors(cfg["seed"], len(cuts) - 1, lo, hi)).cuda()
+        G_dev = torch.empty((len(member), d), dtype=torch.float32, device="cuda")
+        for q, idx in enumerate(member):                 # input preparation: redundant copies of a row range must agree
+            G_dev[q] = atoms_dev[idx].sum(dim=0)
+        del atoms_dev
+        w_dev = torch.zeros(d, dtype=torch.float32, device="cuda")
+    else:
+        data = wl.make_dataset(cfg, threads=min(16, os.cpu_count() or 8))
+        X = data["X"]
+        X_dev = torch.from_numpy(X.view(np.int16) if X.dtype == np.uint16 else X).cuda()
+        y_dev = torch.from_numpy(data["y"]).cuda()
+        w_dev = torch.from_numpy(data["w0"]).cuda()
+    log(f"inputs ready in {time.perf_counter() - t0:.1f}s")
+    ws = cr.Workspace(plan)
+    info = ws.info
+    g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
+    rng = wl.mask_stream(cfg)
+    lr = float(cfg["lr"])
+
+    def step(mask):
+        if aggregate:
+            cr.cr_load_partial_grads(plan, G_dev)
+        else:
+            cr.cr_partial_grads(plan, X_dev, y_dev, w_dev)
+        cr.cr_encode_tree(plan, mask)
+        cr.cr_decode_root(plan, g_dev)
+        if not aggregate:
+            cr.cr_gd_update(plan, w_dev, g_dev, lr)
+
+    for _ in range(args.warmup):
+        step(wl.draw_mask(rng, L, n, s))
+    torch.cuda.synchronize()
+    cr.cr_profile_enable(plan, True)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(wl.draw_mask(rng, L, n, s))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    kernels = {}
+    for kid, name in enumerate(KERNEL_NAMES):
+        ms, launches, nbytes = cr.cr_profile_read(plan, kid)
+        if launches:
+            kernels[name] = {"avg_ms": ms / launches, "launches": launches, "algorithmic_bytes_per_launch": nbytes // launches,
+                             "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None}
+    cr.cr_profile_enable(plan, False)
+
+    dominant = "encode" if aggregate else "partial_grads"
+    dk = kernels[dominant]
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["algorithmic_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS, "traffic": load_traffic(args.workload),
+                "avg_kernel_ms": dk["avg_ms"], "algorithmic_bytes_per_launch": dk["algorithmic_bytes_per_launch"]}
+
+    # ---- CPU baseline: the oracle on the host cores, same inputs, bounded; also a parity check of one more GPU iteration
+    baseline, parity = None, None
+    if args.cpu_budget > 0 and not aggregate:
+        mask = wl.draw_mask(rng, L, n, s)
+        w_host = w_dev.cpu().numpy().copy()
+        cr.cr_partial_grads(plan, X_dev, y_dev, w_dev)
+        cr.cr_encode_tree(plan, mask)
+        cr.cr_decode_root(plan, g_dev)
+        cr.cr_synchronize(plan)
+        baseline, parity = cpu_baseline(cfg, data, None, w_host, mask, g_dev.cpu().numpy().astype(np.float64), args.cpu_budget)
+        log(f"cpu baseline: {baseline}")
+
+    total_bytes = sum(k["algorithmic_bytes_per_launch"] for k in kernels.values())
+    out = {
+        "metric": "CR gradient iterations/sec",
+        "value": args.steps / elapsed,
+        "unit": "iterations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg["x_dtype"] == wl.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {DESCRIPTIONS[args.workload]}", "L": L, "n": n, "s": s, "m": m, "d": d,
+                   "workers": info.num_workers, "slabs": info.num_slabs, "row_visits": info.row_visits,
+                   "stage1_teams": info.num_teams, "stage1_pieces": info.num_pieces, "code_gamma": info.gamma},
+        "algorithmic_GBps_whole_step": total_bytes / (elapsed / args.steps) / 1e9,
+        "hbm_frac_whole_step": total_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": baseline,
+        "parity_rel_l2_vs_oracle": parity,
+    }
+    print(json.dumps(out), flush=True)
+    cr.cr_plan_destroy(plan)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,153 @@
+/* CodedReduce (CR) gradient aggregation: the data-parallel hot path on one AMD MI355X (gfx950).
+ *
+ * All N workers of an (n,L)-regular tree are simulated on one GPU.  One iteration is
+ *
+ *     cr_partial_grads(X, y, w)   every worker's partial gradients over its allocated row segments
+ *     cr_encode_tree(mask)        every non-straggling node's message, leaves first
+ *     cr_decode_root(g)           the master's decode from any n-s of its n children
+ *
+ * and returns the exact full gradient  g = sum over all m data points of the per-point loss
+ * gradient  (Section II-A, eq. (3)) whenever no sibling group has more than s stragglers.
+ *
+ * Notation: m data points (the paper's d), model dimension d (the paper's p), n children per
+ * parent, L layers, s stragglers tolerated per sibling group, N = n + n^2 + ... + n^L workers.
+ * Workers are numbered 0-based level by level: node (l,i), l in 1..L, i in 0..n^l-1, has id
+ * n + ... + n^(l-1) + i and children (l+1, n*i + j), j in 0..n-1; sibling group g is ids [g*n, (g+1)*n),
+ * group 0 being the master's children.
+ *
+ * Conventions for every call
+ *   - plain C ABI; every function returns a cr_status (CR_OK = 0, negatives are errors); the text of the
+ *     last error on the calling thread is available from cr_last_error().
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *   - the caller owns X, y, w, g and the workspace block; the library allocates no device memory and
+ *     frees nothing it was handed.  A plan owns only host tables (and a few KB of pinned host staging
+ *     once a workspace is bound).
+ *   - device work is enqueued on the stream given to cr_bind_workspace and the call returns without
+ *     waiting, unless stated otherwise.
+ *   - a plan is not thread-safe; calls on one plan that overlap in time race.
+ */
+#ifndef CODEDREDUCE_H
+#define CODEDREDUCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cr_plan_s cr_plan_t;
+
+enum cr_status {
+    CR_OK = 0,
+    CR_E_INVAL = -1,        /* bad argument, unsupported size, workspace too small or not bound */
+    CR_E_UNDECODABLE = -2,  /* some sibling group has more than s stragglers (remark after Theorem 1) */
+    CR_E_STATE = -3,        /* call out of order: encode before gradients exist, decode before encode */
+    CR_E_HIP = -4,          /* a HIP runtime call failed; see cr_last_error() */
+    CR_E_NOMEM = -5         /* host allocation failed */
+};
+
+enum cr_model {
+    CR_LINEAR = 0,          /* least squares:  per-point gradient x (x.w - y) */
+    CR_LOGISTIC = 1,        /* logistic loss, targets y in {0,1}:  x (sigmoid(x.w) - y) */
+    CR_AGGREGATE_ONLY = 2   /* no data matrix: partial gradients are supplied by cr_load_partial_grads */
+};
+
+enum cr_xdtype { CR_F32 = 0, CR_BF16 = 1 }; /* storage type of X only; y, w, g, slabs and messages are fp32 */
+
+enum cr_kernel {            /* ids for cr_profile_read */
+    CR_K_PARTIAL_GRADS = 0, CR_K_REDUCE_PIECES = 1, CR_K_ENCODE = 2, CR_K_DECODE = 3, CR_K_UPDATE = 4, CR_K_COUNT = 5
+};
+
+typedef struct cr_plan_info {
+    int32_t L, n, s, model, x_dtype;
+    int32_t num_workers;     /* N */
+    int32_t num_groups;      /* N / n sibling groups */
+    int32_t num_slabs;       /* S: (worker, segment) pairs; one d-float partial gradient each */
+    int32_t num_decode_rows; /* F = C(n,s) */
+    int32_t code_candidate;  /* index of the winning candidate of the code search, -1 if B was supplied */
+    int32_t num_teams;       /* stage-1 work split (0 until known, see cr_plan_set_teams) */
+    int32_t num_pieces;      /* stage-1 partial rows (0 until the split is known) */
+    int64_t m, d;
+    int64_t row_visits;      /* sum over workers of allocated rows */
+    int64_t min_rows, max_rows; /* smallest / largest per-worker load; both equal r_CR m up to integer cuts (Theorem 1) */
+    double gamma;            /* max_f sum_i |a_fi| ||b_i||_2 / sqrt(n): rounding amplification of one decode */
+    double r_cr;             /* computation load of Theorem 1 */
+} cr_plan_info_t;
+
+/* ---- plan (host only; Section III-A CR.Allocate, Algorithms 1 and 2, Section II-C for the code) ------------
+ * cr_plan builds, on the host: the gradient-coding matrices B (n x n, cyclic support {i..i+s} mod n, unit-norm
+ * rows) and the decode rows a_f (a_f B = 1, zero on the straggler set); the recursive allocation of weighted row
+ * segments to every node (CompAlloc with k = n parts cut at floor(kappa |W| / n); a node keeps the first
+ * round(|W| / sum_{j=0}^{L-l} (n/(s+1))^j) positions of its sub-tree set, leaves keep all); and the slab list
+ * (node-major, segments in allocation order).  cr_plan = cr_plan_ex with CR_LINEAR, CR_F32, the default seed, no B.
+ *   seed         seeds the counter-based search for a well-conditioned code (ignored when B is given)
+ *   B_or_null    host, n*n doubles row-major: use this encoding matrix (support must be the cyclic window); or NULL
+ *   out          receives the plan; destroy with cr_plan_destroy
+ * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, m<N, C(n,s) > 2^20, N > 2^24, a singular/unsupported B. */
+int cr_plan(int L, int n, int s, int64_t m, int64_t d, cr_plan_t **out);
+int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype, uint64_t seed,
+               const double *B_or_null, cr_plan_t **out);
+void cr_plan_destroy(cr_plan_t *plan);
+
+/* ---- introspection (host; data for tests and harnesses) ------------------------------------------------------ */
+int cr_plan_info(const cr_plan_t *plan, cr_plan_info_t *info);
+int cr_plan_get_B(const cr_plan_t *plan, double *B /* host, n*n */);
+int cr_plan_get_A(const cr_plan_t *plan, double *A /* host, F*n, row f = f-th straggler set in lexicographic order */);
+/* slab p: worker node[p] holds rows [row_begin[p], row_end[p]) of X with combining coefficient coef[p]; arrays of S entries, any may be NULL */
+int cr_plan_get_slabs(const cr_plan_t *plan, int32_t *node, int64_t *row_begin, int64_t *row_end, double *coef);
+/* decode row for one sibling group (Section III-A, CR.Execute step 3): flags[j] != 0 marks child j a straggler.  With fewer than
+ * s stragglers the set is padded with the highest-index survivors.  a: host, n doubles.  CR_E_UNDECODABLE if more than s are set. */
+int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */, double *a);
+/* Stage-1 work split: the row visits of all slabs, slab-major, are cut into `teams` equal contiguous ranges; a range that crosses a
+ * slab boundary is cut there, giving the pieces.  Chosen from the device at cr_workspace_bytes unless set here first (teams >= 1). */
+int cr_plan_set_teams(cr_plan_t *plan, int teams);
+int cr_plan_get_pieces(const cr_plan_t *plan, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team); /* num_pieces entries each */
+
+/* ---- device binding --------------------------------------------------------------------------------------------
+ * The workspace holds the device tables, the per-call encode program, the stage-1 piece partials, the slab gradients
+ * G[S][d] (not for CR_AGGREGATE_ONLY) and the messages M[N][d], all fp32 rows of d floats.  cr_workspace_bytes needs a
+ * current HIP device unless cr_plan_set_teams was called.  dev_ptr must be 256-byte aligned and stay valid while the plan
+ * is used; hip_stream is a hipStream_t (NULL = the default stream).  cr_bind_workspace copies the tables synchronously. */
+int cr_workspace_bytes(cr_plan_t *plan, size_t *bytes);
+int cr_bind_workspace(cr_plan_t *plan, void *dev_ptr, size_t bytes, void *hip_stream);
+
+/* ---- the hot path ------------------------------------------------------------------------------------------------
+ * cr_partial_grads (CR.Execute step 1): for every slab p,  G[p] = X[b:e]^T (phi(X[b:e] w) - y[b:e]),  phi = identity or sigmoid.
+ *   X_dev  m x d row-major, contiguous, fp32 or bf16 per the plan, 16-byte aligned;  y_dev m floats;  w_dev d floats.
+ *   Every holder of a row reads it itself (the redundancy is the method); X is read once per holder.
+ * cr_load_partial_grads: use caller-supplied slab gradients G_dev[S][d] (fp32, 16-byte aligned) in place of stage 1;
+ *   the buffer is read in place by cr_encode_tree and must stay valid until then.
+ * cr_encode_tree (CR.Execute steps 2-5): mask is HOST memory, N bytes, non-zero = straggler.  For every non-straggler node,
+ *   m_(l,i) = sum_p coef_p G[p] over its slabs  +  sum_j a_j m_(l+1, n i + j)  with a = the decode row of its children group.
+ *   Stragglers write no message (their row of M keeps stale data); all other nodes do, also below a straggler.
+ *   CR_E_UNDECODABLE, before anything is enqueued and with no state change, if any group has more than s stragglers.
+ * cr_decode_root: g_dev[d] = sum_j a_j m_(1,j) with the decode row of group 0 from the last cr_encode_tree.
+ * cr_gd_update: w <- w - lr * g (plain gradient step used by the benchmark loop).
+ * Errors: CR_E_STATE out of order; CR_E_INVAL unbound workspace / NULL / misaligned pointers; CR_E_HIP launch failures. */
+int cr_partial_grads(cr_plan_t *plan, const void *X_dev, const float *y_dev, const float *w_dev);
+int cr_load_partial_grads(cr_plan_t *plan, const float *G_dev);
+int cr_encode_tree(cr_plan_t *plan, const uint8_t *straggler_mask_host);
+int cr_decode_root(cr_plan_t *plan, float *g_dev);
+int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
+
+/* ---- results kept in the workspace (device pointers, valid while the workspace is) --------------------------- */
+int cr_get_slab_grads(const cr_plan_t *plan, const float **G_dev); /* S x d */
+int cr_get_messages(const cr_plan_t *plan, const float **M_dev);   /* N x d, row = worker id */
+
+/* ---- timing ---------------------------------------------------------------------------------------------------------
+ * With profiling enabled every kernel launch is bracketed by HIP events on the bound stream.  cr_profile_read waits for the
+ * stream, then returns for one kernel id the summed duration, the number of launches and the algorithmic bytes of those launches
+ * (bytes the method must move: rows read once per holder, each result written once) since profiling was enabled; any may be NULL. */
+int cr_profile_enable(cr_plan_t *plan, int enable);
+int cr_profile_read(cr_plan_t *plan, int kernel, double *total_ms, int64_t *launches, int64_t *algorithmic_bytes);
+/* algorithmic bytes of the most recent launch of a kernel id (0 if none yet) */
+int cr_last_algorithmic_bytes(const cr_plan_t *plan, int kernel, int64_t *bytes);
+int cr_synchronize(cr_plan_t *plan); /* wait for the bound stream */
+
+const char *cr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODEDREDUCE_H */

@@ -1,0 +1,628 @@
+// C-ABI boundary of the CodedReduce hot path: plan (host), workspace binding, and the three stages of one iteration.
+#include "codedreduce.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "gc_design.h"
+#include "kernels.h"
+#include "tree_plan.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(CR_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define CR_HIP(call)                                        \
+    do {                                                    \
+        hipError_t e_ = (call);                             \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);   \
+    } while (0)
+
+constexpr uint64_t kDefaultSeed = 190201981ull;
+constexpr int kStagingSlots = 4;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct TimedLaunch {
+    int kernel;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct cr_plan_s {
+    // problem
+    int L = 0, n = 0, s = 0, model = 0, x_dtype = 0;
+    int64_t m = 0, d = 0;
+    cr::Tree tree;
+    cr::GcCode code;
+    std::vector<cr::WeightedSet> own;
+    std::vector<cr::Slab> slabs;
+    std::vector<int32_t> node_slab_begin;          // N+1
+    int64_t row_visits = 0, min_rows = 0, max_rows = 0;
+    mutable std::unordered_map<uint64_t, std::vector<double>> row_cache;   // padded straggler bitmask -> decode row
+
+    // stage-1 split
+    const cr::Stage1Variant *variant = nullptr;
+    int teams = 0;
+    std::vector<cr::Piece> pieces;
+    std::vector<int32_t> slab_piece_begin, team_piece_begin;
+
+    // device binding
+    bool bound = false;
+    hipStream_t stream = nullptr;
+    char *ws = nullptr;
+    size_t ws_bytes = 0;
+    cr::DevPiece *d_pieces = nullptr;
+    int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr;
+    char *d_program = nullptr;                     // per-call encode program + root decode terms
+    size_t program_bytes = 0;
+    float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr;
+    const float *G_src = nullptr;                  // slabs the encode reads: d_G or the caller's buffer
+    char *h_staging = nullptr;                     // pinned, kStagingSlots * program_bytes
+    hipEvent_t staging_done[kStagingSlots] = {};
+    bool staging_used[kStagingSlots] = {};
+    int staging_next = 0;
+    // layout of the program block (offsets in bytes, fixed per plan)
+    size_t off_terms = 0, off_fins = 0, off_sub = 0, off_dec = 0;
+    size_t max_terms = 0, max_fins = 0;
+    int num_dec_terms = 0;
+
+    bool have_grads = false, have_messages = false;
+
+    // timing
+    bool profiling = false;
+    std::vector<TimedLaunch> timed;
+    std::vector<hipEvent_t> event_pool;
+    double total_ms[CR_K_COUNT] = {};
+    int64_t launches[CR_K_COUNT] = {}, bytes_sum[CR_K_COUNT] = {}, bytes_last[CR_K_COUNT] = {};
+};
+
+namespace {
+
+int64_t elem_size(const cr_plan_t *p) { return p->x_dtype == CR_BF16 ? 2 : 4; }
+
+// decode row for one group under rule "pad with the highest-index survivors"; returns CR_E_UNDECODABLE if more than s flags are set
+int group_decode_row(const cr_plan_t *p, const uint8_t *flags, const double **row)
+{
+    uint64_t bits = 0;
+    int cnt = 0;
+    for (int j = 0; j < p->n; ++j)
+        if (flags[j]) { bits |= 1ull << j; ++cnt; }
+    if (cnt > p->s) return CR_E_UNDECODABLE;
+    for (int j = p->n - 1; cnt < p->s; --j)
+        if (!((bits >> j) & 1ull)) { bits |= 1ull << j; ++cnt; }
+    auto it = p->row_cache.find(bits);
+    if (it == p->row_cache.end()) {
+        std::vector<double> a(p->n);
+        if (!cr::decode_row(p->code, bits, a.data())) return fail(CR_E_INVAL, "decode row: survivor system is inconsistent");
+        it = p->row_cache.emplace(bits, std::move(a)).first;
+    }
+    *row = it->second.data();
+    return CR_OK;
+}
+
+int ensure_split(cr_plan_t *p)
+{
+    if (!p->pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
+    if (!p->variant) return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels");
+    if (p->teams <= 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        CR_HIP(hipGetDevice(&dev));
+        CR_HIP(hipGetDeviceProperties(&prop, dev));
+        int per_cu = 0;
+        CR_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn, p->variant->block(), 0));
+        if (per_cu < 1) per_cu = 1;
+        int oversub = 1;
+        if (const char *e = std::getenv("CR_STAGE1_OVERSUB")) oversub = std::max(1, std::atoi(e));
+        int64_t teams = static_cast<int64_t>(prop.multiProcessorCount) * per_cu * p->variant->teams_per_block() * oversub;
+        p->teams = static_cast<int>(std::min<int64_t>(teams, std::max<int64_t>(1, p->row_visits)));
+    }
+    cr::split_pieces(p->slabs, p->teams, p->pieces, p->slab_piece_begin, p->team_piece_begin);
+    return CR_OK;
+}
+
+void compute_layout(cr_plan_t *p, size_t *total)
+{
+    const size_t S = p->slabs.size(), N = p->tree.N, P = p->pieces.size();
+    // worst case: one term per slab plus one dummy per node, each sub-program padded to the unroll
+    p->max_terms = S + N + static_cast<size_t>(p->n) * cr::kEncodeUnroll;
+    p->max_fins = N;
+    size_t off = 0;
+    p->off_terms = off; off = align_up(off + p->max_terms * sizeof(cr::EncTerm), 256);
+    p->off_fins = off;  off = align_up(off + p->max_fins * sizeof(cr::EncFin), 256);
+    p->off_sub = off;   off = align_up(off + (p->n + 1) * sizeof(int32_t), 256);
+    p->off_dec = off;   off = align_up(off + p->n * sizeof(cr::DecTerm), 256);
+    p->program_bytes = off;
+
+    size_t w = 0;
+    w = align_up(w + P * sizeof(cr::DevPiece), 256);
+    w = align_up(w + (p->teams + 1) * sizeof(int32_t), 256);
+    w = align_up(w + (S + 1) * sizeof(int32_t), 256);
+    w = align_up(w + p->program_bytes, 256);
+    const size_t row = static_cast<size_t>(p->d) * sizeof(float);
+    if (p->model != CR_AGGREGATE_ONLY) {
+        w = align_up(w + P * row, 256);
+        w = align_up(w + S * row, 256);
+    }
+    w = align_up(w + N * row, 256);
+    *total = w;
+}
+
+hipEvent_t take_event(cr_plan_t *p)
+{
+    if (!p->event_pool.empty()) {
+        hipEvent_t e = p->event_pool.back();
+        p->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct LaunchTimer {     // brackets one launch with events when profiling is on
+    cr_plan_t *p;
+    int kernel;
+    hipEvent_t start = nullptr, stop = nullptr;
+    LaunchTimer(cr_plan_t *plan, int k, int64_t bytes) : p(plan), kernel(k)
+    {
+        p->bytes_last[k] = bytes;
+        if (!p->profiling) return;
+        start = take_event(p);
+        stop = take_event(p);
+        if (start && stop) (void)hipEventRecord(start, p->stream);
+    }
+    void done()
+    {
+        if (!p->profiling || !start || !stop) return;
+        (void)hipEventRecord(stop, p->stream);
+        p->timed.push_back({kernel, start, stop});
+        p->bytes_sum[kernel] += p->bytes_last[kernel];
+    }
+};
+
+int fold_timings(cr_plan_t *p)
+{
+    for (const TimedLaunch &t : p->timed) {
+        float ms = 0.f;
+        CR_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
+        p->total_ms[t.kernel] += ms;
+        p->launches[t.kernel] += 1;
+        p->event_pool.push_back(t.start);
+        p->event_pool.push_back(t.stop);
+    }
+    p->timed.clear();
+    return CR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *cr_last_error(void) { return g_last_error.c_str(); }
+
+int cr_plan(int L, int n, int s, int64_t m, int64_t d, cr_plan_t **out)
+{
+    return cr_plan_ex(L, n, s, m, d, CR_LINEAR, CR_F32, kDefaultSeed, nullptr, out);
+}
+
+int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype, uint64_t seed, const double *B_or_null, cr_plan_t **out)
+{
+    if (!out) return fail(CR_E_INVAL, "out is NULL");
+    *out = nullptr;
+    if (L < 1 || L > cr::kMaxLevels) return fail(CR_E_INVAL, "L must be in 1..8");
+    if (n < 2 || n > 64) return fail(CR_E_INVAL, "n must be in 2..64");
+    if (s < 0 || s >= n) return fail(CR_E_INVAL, "s must be in 0..n-1");
+    if (d < 1) return fail(CR_E_INVAL, "d must be positive");
+    if (model < CR_LINEAR || model > CR_AGGREGATE_ONLY) return fail(CR_E_INVAL, "unknown model");
+    if (x_dtype != CR_F32 && x_dtype != CR_BF16) return fail(CR_E_INVAL, "unknown x_dtype");
+    if (cr::num_straggler_sets(n, s, int64_t(1) << 20) < 0) return fail(CR_E_INVAL, "C(n,s) exceeds 2^20 straggler patterns");
+    cr_plan_t *p = new (std::nothrow) cr_plan_s();
+    if (!p) return fail(CR_E_NOMEM, "out of host memory");
+    try {
+        if (!cr::make_tree(n, L, p->tree)) { delete p; return fail(CR_E_INVAL, "tree has more than 2^24 workers"); }
+        if (m < p->tree.N) { delete p; return fail(CR_E_INVAL, "m must be at least the number of workers"); }
+        if (m > (int64_t(1) << 40)) { delete p; return fail(CR_E_INVAL, "m exceeds 2^40"); }
+        p->L = L; p->n = n; p->s = s; p->m = m; p->d = d; p->model = model; p->x_dtype = x_dtype;
+        bool ok = B_or_null ? cr::adopt_code(n, s, B_or_null, p->code) : cr::design_code(n, s, seed, p->code);
+        if (!ok) { delete p; return fail(CR_E_INVAL, B_or_null ? "supplied B has the wrong support or does not decode" : "code search found no usable candidate"); }
+        cr::allocate(p->tree, s, m, p->code.B.data(), p->own, p->slabs);
+        p->node_slab_begin.assign(p->tree.N + 1, 0);
+        for (const cr::Slab &sl : p->slabs) p->node_slab_begin[sl.node + 1] += 1;
+        for (int32_t i = 0; i < p->tree.N; ++i) p->node_slab_begin[i + 1] += p->node_slab_begin[i];
+        p->min_rows = INT64_MAX;
+        for (int32_t node = 0; node < p->tree.N; ++node) {
+            int64_t rows = 0;
+            for (const cr::Segment &g : p->own[node]) rows += g.row_end - g.row_begin;
+            p->row_visits += rows;
+            p->min_rows = std::min(p->min_rows, rows);
+            p->max_rows = std::max(p->max_rows, rows);
+        }
+        if (p->slabs.size() > (size_t(1) << 30)) { delete p; return fail(CR_E_INVAL, "too many slabs"); }
+        if (model != CR_AGGREGATE_ONLY) {
+            p->variant = cr::select_stage1(x_dtype, d);
+            if (!p->variant) { delete p; return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels (d <= 24576 when d is a multiple of 4 (fp32) or 8 (bf16), else d <= 6144)"); }
+        }
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(CR_E_NOMEM, "out of host memory");
+    }
+    *out = p;
+    return CR_OK;
+}
+
+void cr_plan_destroy(cr_plan_t *p)
+{
+    if (!p) return;
+    if (p->bound) (void)hipStreamSynchronize(p->stream);
+    for (const TimedLaunch &t : p->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    for (hipEvent_t e : p->event_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : p->staging_done)
+        if (e) (void)hipEventDestroy(e);
+    if (p->h_staging) (void)hipHostFree(p->h_staging);
+    delete p;
+}
+
+int cr_plan_info(const cr_plan_t *p, cr_plan_info_t *info)
+{
+    if (!p || !info) return fail(CR_E_INVAL, "NULL argument");
+    std::memset(info, 0, sizeof *info);
+    info->L = p->L; info->n = p->n; info->s = p->s; info->model = p->model; info->x_dtype = p->x_dtype;
+    info->num_workers = p->tree.N;
+    info->num_groups = p->tree.N / p->n;
+    info->num_slabs = static_cast<int32_t>(p->slabs.size());
+    info->num_decode_rows = static_cast<int32_t>(cr::num_straggler_sets(p->n, p->s, int64_t(1) << 20));
+    info->code_candidate = p->code.candidate;
+    info->num_teams = p->pieces.empty() ? 0 : p->teams;
+    info->num_pieces = static_cast<int32_t>(p->pieces.size());
+    info->m = p->m; info->d = p->d;
+    info->row_visits = p->row_visits;
+    info->min_rows = p->min_rows; info->max_rows = p->max_rows;
+    info->gamma = p->code.gamma;
+    double q = static_cast<double>(p->n) / (p->s + 1), sum = 0.0, pw = 1.0;
+    for (int l = 1; l <= p->L; ++l) { pw *= q; sum += pw; }
+    info->r_cr = 1.0 / sum;
+    return CR_OK;
+}
+
+int cr_plan_get_B(const cr_plan_t *p, double *B)
+{
+    if (!p || !B) return fail(CR_E_INVAL, "NULL argument");
+    std::copy(p->code.B.begin(), p->code.B.end(), B);
+    return CR_OK;
+}
+
+int cr_plan_get_A(const cr_plan_t *p, double *A)
+{
+    if (!p || !A) return fail(CR_E_INVAL, "NULL argument");
+    const int64_t F = cr::num_straggler_sets(p->n, p->s, int64_t(1) << 20);
+    for (int64_t f = 0; f < F; ++f)
+        if (!cr::decode_row(p->code, cr::straggler_set_by_rank(p->n, p->s, f), A + f * p->n))
+            return fail(CR_E_INVAL, "decode row: survivor system is inconsistent");
+    return CR_OK;
+}
+
+int cr_plan_get_slabs(const cr_plan_t *p, int32_t *node, int64_t *row_begin, int64_t *row_end, double *coef)
+{
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    for (size_t i = 0; i < p->slabs.size(); ++i) {
+        if (node) node[i] = p->slabs[i].node;
+        if (row_begin) row_begin[i] = p->slabs[i].row_begin;
+        if (row_end) row_end[i] = p->slabs[i].row_end;
+        if (coef) coef[i] = p->slabs[i].coef;
+    }
+    return CR_OK;
+}
+
+int cr_plan_decode_row(const cr_plan_t *p, const uint8_t *flags, double *a)
+{
+    if (!p || !flags || !a) return fail(CR_E_INVAL, "NULL argument");
+    const double *row = nullptr;
+    int rc = group_decode_row(p, flags, &row);
+    if (rc == CR_E_UNDECODABLE) return fail(rc, "more than s stragglers in the group");
+    if (rc != CR_OK) return rc;
+    std::copy(row, row + p->n, a);
+    return CR_OK;
+}
+
+int cr_plan_set_teams(cr_plan_t *p, int teams)
+{
+    if (!p || teams < 1) return fail(CR_E_INVAL, "teams must be >= 1");
+    if (p->bound) return fail(CR_E_STATE, "the work split cannot change once a workspace is bound");
+    if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_INVAL, "an aggregation-only plan has no stage-1 split");
+    p->teams = static_cast<int>(std::min<int64_t>(teams, p->row_visits));
+    p->pieces.clear();
+    return ensure_split(p);
+}
+
+int cr_plan_get_pieces(const cr_plan_t *p, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team)
+{
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    for (size_t i = 0; i < p->pieces.size(); ++i) {
+        if (slab) slab[i] = p->pieces[i].slab;
+        if (row_begin) row_begin[i] = p->pieces[i].row_begin;
+        if (row_end) row_end[i] = p->pieces[i].row_end;
+        if (team) team[i] = p->pieces[i].team;
+    }
+    return CR_OK;
+}
+
+int cr_workspace_bytes(cr_plan_t *p, size_t *bytes)
+{
+    if (!p || !bytes) return fail(CR_E_INVAL, "NULL argument");
+    int rc = ensure_split(p);
+    if (rc != CR_OK) return rc;
+    compute_layout(p, bytes);
+    return CR_OK;
+}
+
+int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_stream)
+{
+    if (!p || !dev_ptr) return fail(CR_E_INVAL, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) % 256 != 0) return fail(CR_E_INVAL, "workspace must be 256-byte aligned");
+    int rc = ensure_split(p);
+    if (rc != CR_OK) return rc;
+    size_t need = 0;
+    compute_layout(p, &need);
+    if (bytes < need) return fail(CR_E_INVAL, "workspace too small");
+    if (p->bound) CR_HIP(hipStreamSynchronize(p->stream));
+    p->stream = static_cast<hipStream_t>(hip_stream);
+    p->ws = static_cast<char *>(dev_ptr);
+    p->ws_bytes = bytes;
+
+    const size_t S = p->slabs.size(), N = p->tree.N, P = p->pieces.size();
+    const size_t row = static_cast<size_t>(p->d) * sizeof(float);
+    size_t w = 0;
+    p->d_pieces = reinterpret_cast<cr::DevPiece *>(p->ws + w);             w = align_up(w + P * sizeof(cr::DevPiece), 256);
+    p->d_team_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (p->teams + 1) * sizeof(int32_t), 256);
+    p->d_slab_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (S + 1) * sizeof(int32_t), 256);
+    p->d_program = p->ws + w;                                              w = align_up(w + p->program_bytes, 256);
+    p->d_partial = nullptr; p->d_G = nullptr;
+    if (p->model != CR_AGGREGATE_ONLY) {
+        p->d_partial = reinterpret_cast<float *>(p->ws + w);               w = align_up(w + P * row, 256);
+        p->d_G = reinterpret_cast<float *>(p->ws + w);                     w = align_up(w + S * row, 256);
+    }
+    p->d_M = reinterpret_cast<float *>(p->ws + w);                         w = align_up(w + N * row, 256);
+    p->G_src = p->d_G;
+
+    if (P > 0) {
+        std::vector<cr::DevPiece> hp(P);
+        for (size_t i = 0; i < P; ++i)
+            hp[i] = {p->pieces[i].row_begin, static_cast<int32_t>(p->pieces[i].row_end - p->pieces[i].row_begin), p->pieces[i].slab};
+        CR_HIP(hipMemcpy(p->d_pieces, hp.data(), P * sizeof(cr::DevPiece), hipMemcpyHostToDevice));
+        CR_HIP(hipMemcpy(p->d_team_piece_begin, p->team_piece_begin.data(), (p->teams + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+        CR_HIP(hipMemcpy(p->d_slab_piece_begin, p->slab_piece_begin.data(), (S + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+    if (!p->h_staging) {
+        CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kStagingSlots, hipHostMallocDefault));
+        for (int i = 0; i < kStagingSlots; ++i) CR_HIP(hipEventCreateWithFlags(&p->staging_done[i], hipEventDisableTiming));
+    }
+    p->bound = true;
+    p->have_grads = false;
+    p->have_messages = false;
+    return CR_OK;
+}
+
+int cr_partial_grads(cr_plan_t *p, const void *X, const float *y, const float *w)
+{
+    if (!p || !X || !y || !w) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_STATE, "aggregation-only plan: use cr_load_partial_grads");
+    if (reinterpret_cast<uintptr_t>(X) % 16 != 0) return fail(CR_E_INVAL, "X must be 16-byte aligned");
+    const int64_t S = static_cast<int64_t>(p->slabs.size()), P = static_cast<int64_t>(p->pieces.size());
+    {
+        const int64_t bytes = p->row_visits * p->d * elem_size(p) + p->row_visits * 4 + P * p->d * 4 + p->d * 4;
+        LaunchTimer t(p, CR_K_PARTIAL_GRADS, bytes);
+        CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->teams, p->d_partial, p->d,
+                                        p->model == CR_LOGISTIC ? 1 : 0, p->stream));
+        t.done();
+    }
+    {
+        LaunchTimer t(p, CR_K_REDUCE_PIECES, (P + S) * p->d * 4);
+        CR_HIP(cr::launch_reduce_pieces(p->d_partial, p->d_slab_piece_begin, static_cast<int>(S), p->d_G, p->d, p->stream));
+        t.done();
+    }
+    p->G_src = p->d_G;
+    p->have_grads = true;
+    p->have_messages = false;
+    return CR_OK;
+}
+
+int cr_load_partial_grads(cr_plan_t *p, const float *G)
+{
+    if (!p || !G) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (reinterpret_cast<uintptr_t>(G) % 16 != 0) return fail(CR_E_INVAL, "G must be 16-byte aligned");
+    p->G_src = G;
+    p->have_grads = true;
+    p->have_messages = false;
+    return CR_OK;
+}
+
+int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
+{
+    if (!p || !mask) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (!p->have_grads) return fail(CR_E_STATE, "no partial gradients yet");
+    const int n = p->n, L = p->L;
+    const int32_t N = p->tree.N, groups = N / n;
+
+    // decode row of every sibling group; any group beyond tolerance fails the call before anything is enqueued
+    std::vector<const double *> rows(groups);
+    for (int32_t g = 0; g < groups; ++g) {
+        int rc = group_decode_row(p, mask + static_cast<size_t>(g) * n, &rows[g]);
+        if (rc == CR_E_UNDECODABLE) return fail(rc, "sibling group " + std::to_string(g) + " has more than s stragglers");
+        if (rc != CR_OK) return rc;
+    }
+
+    // host staging slot (pinned); wait until the copy that last used it has finished
+    const int slot = p->staging_next;
+    p->staging_next = (slot + 1) % kStagingSlots;
+    if (p->staging_used[slot]) CR_HIP(hipEventSynchronize(p->staging_done[slot]));
+    char *h = p->h_staging + static_cast<size_t>(slot) * p->program_bytes;
+    cr::EncTerm *terms = reinterpret_cast<cr::EncTerm *>(h + p->off_terms);
+    cr::EncFin *fins = reinterpret_cast<cr::EncFin *>(h + p->off_fins);
+    int32_t *sub = reinterpret_cast<int32_t *>(h + p->off_sub);
+    cr::DecTerm *dec = reinterpret_cast<cr::DecTerm *>(h + p->off_dec);
+
+    // post-order program of every level-1 sub-tree
+    size_t nt = 0, nf = 0;
+    int64_t active_slabs = 0, active_msgs = 0;
+    struct Frame { int32_t node; int level; int next_child; };
+    std::vector<Frame> stack;
+    for (int i = 0; i < n; ++i) {
+        sub[i] = static_cast<int32_t>(nt);
+        stack.push_back({static_cast<int32_t>(i), 1, 0});
+        while (!stack.empty()) {
+            Frame &f = stack.back();
+            if (f.level < L && f.next_child < n) {
+                const int32_t child = p->tree.level_offset[f.level + 1] + (f.node - p->tree.level_offset[f.level]) * n + f.next_child;
+                ++f.next_child;
+                stack.push_back({child, f.level + 1, 0});
+                continue;
+            }
+            const int32_t node = f.node;
+            const int level = f.level;
+            stack.pop_back();
+            if (mask[node]) continue;                     // a straggler sends nothing
+            double acoef = 0.0;
+            if (level >= 2) {
+                const int32_t parent = p->tree.level_offset[level - 1] + (node - p->tree.level_offset[level]) / n;
+                if (!mask[parent]) acoef = rows[node / n][node % n];
+            }
+            const int32_t sb = p->node_slab_begin[node], se = p->node_slab_begin[node + 1];
+            for (int32_t q = sb; q < se; ++q) terms[nt++] = {q, -1, p->slabs[q].coef};
+            if (se == sb) terms[nt++] = {0, -1, 0.0};     // a node without rows still sends its children's combination
+            terms[nt - 1].fin = static_cast<int32_t>(nf);
+            fins[nf++] = {level, node, acoef};
+            active_slabs += se - sb;
+            active_msgs += 1;
+        }
+        while (nt % cr::kEncodeUnroll != 0) {             // pad with no-op terms on an already fetched slab
+            terms[nt] = {nt > 0 ? terms[nt - 1].slab : 0, -1, 0.0};
+            ++nt;
+        }
+    }
+    sub[n] = static_cast<int32_t>(nt);
+    int ndec = 0;
+    for (int j = 0; j < n; ++j)
+        if (!mask[j] && rows[0][j] != 0.0) dec[ndec++] = {j, 0, rows[0][j]};
+    p->num_dec_terms = ndec;
+
+    CR_HIP(hipMemcpyAsync(p->d_program, h, p->program_bytes, hipMemcpyHostToDevice, p->stream));
+    CR_HIP(hipEventRecord(p->staging_done[slot], p->stream));
+    p->staging_used[slot] = true;
+
+    LaunchTimer t(p, CR_K_ENCODE, (active_slabs + active_msgs) * p->d * 4);
+    CR_HIP(cr::launch_encode(p->G_src, p->d_M, reinterpret_cast<const cr::EncTerm *>(p->d_program + p->off_terms),
+                             reinterpret_cast<const cr::EncFin *>(p->d_program + p->off_fins),
+                             reinterpret_cast<const int32_t *>(p->d_program + p->off_sub), n, L, p->d, p->stream));
+    t.done();
+    p->have_messages = true;
+    return CR_OK;
+}
+
+int cr_decode_root(cr_plan_t *p, float *g)
+{
+    if (!p || !g) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (!p->have_messages) return fail(CR_E_STATE, "no messages yet: call cr_encode_tree first");
+    LaunchTimer t(p, CR_K_DECODE, static_cast<int64_t>(p->num_dec_terms + 1) * p->d * 4);
+    CR_HIP(cr::launch_decode(p->d_M, g, reinterpret_cast<const cr::DecTerm *>(p->d_program + p->off_dec), p->num_dec_terms, p->d, p->stream));
+    t.done();
+    return CR_OK;
+}
+
+int cr_gd_update(cr_plan_t *p, float *w, const float *g, float lr)
+{
+    if (!p || !w || !g) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    LaunchTimer t(p, CR_K_UPDATE, 3 * p->d * 4);
+    CR_HIP(cr::launch_update(w, g, lr, p->d, p->stream));
+    t.done();
+    return CR_OK;
+}
+
+int cr_get_slab_grads(const cr_plan_t *p, const float **G)
+{
+    if (!p || !G) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    *G = p->G_src;
+    return CR_OK;
+}
+
+int cr_get_messages(const cr_plan_t *p, const float **M)
+{
+    if (!p || !M) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    *M = p->d_M;
+    return CR_OK;
+}
+
+int cr_profile_enable(cr_plan_t *p, int enable)
+{
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    if (p->bound) {
+        CR_HIP(hipStreamSynchronize(p->stream));
+        int rc = fold_timings(p);
+        if (rc != CR_OK) return rc;
+    }
+    if (enable && !p->profiling) {
+        for (int k = 0; k < CR_K_COUNT; ++k) { p->total_ms[k] = 0.0; p->launches[k] = 0; p->bytes_sum[k] = 0; }
+    }
+    p->profiling = enable != 0;
+    return CR_OK;
+}
+
+int cr_profile_read(cr_plan_t *p, int kernel, double *total_ms, int64_t *launches, int64_t *algorithmic_bytes)
+{
+    if (!p || kernel < 0 || kernel >= CR_K_COUNT) return fail(CR_E_INVAL, "bad argument");
+    if (p->bound) {
+        CR_HIP(hipStreamSynchronize(p->stream));
+        int rc = fold_timings(p);
+        if (rc != CR_OK) return rc;
+    }
+    if (total_ms) *total_ms = p->total_ms[kernel];
+    if (launches) *launches = p->launches[kernel];
+    if (algorithmic_bytes) *algorithmic_bytes = p->bytes_sum[kernel];
+    return CR_OK;
+}
+
+int cr_last_algorithmic_bytes(const cr_plan_t *p, int kernel, int64_t *bytes)
+{
+    if (!p || !bytes || kernel < 0 || kernel >= CR_K_COUNT) return fail(CR_E_INVAL, "bad argument");
+    *bytes = p->bytes_last[kernel];
+    return CR_OK;
+}
+
+int cr_synchronize(cr_plan_t *p)
+{
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    CR_HIP(hipStreamSynchronize(p->stream));
+    return CR_OK;
+}
+
+}  // extern "C"

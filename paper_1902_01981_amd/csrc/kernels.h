@@ -1,0 +1,57 @@
+// Device-side tables and kernel launchers of the CodedReduce hot path (gfx950).  Host code sees only plain launch functions.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+
+namespace cr {
+
+struct DevPiece {            // one stage-1 work item: rows [row_begin, row_begin + nrows) of X, partial row = index of the piece
+    int64_t row_begin;
+    int32_t nrows;
+    int32_t slab;
+};
+
+struct EncTerm {             // own += coef * G[slab]; then, if fin >= 0, finish the node described by fins[fin]
+    int32_t slab;
+    int32_t fin;
+    double coef;
+};
+
+struct EncFin {              // message of a node at `level`: own + pending[level]; stored to M[row]; folded into pending[level-1] with acoef
+    int32_t level;
+    int32_t row;
+    double acoef;
+};
+
+struct DecTerm {             // g += coef * M[row]
+    int32_t row;
+    int32_t pad;
+    double coef;
+};
+
+constexpr int kEncodeUnroll = 8;   // encode sub-programs are padded to a multiple of this many terms
+constexpr int kMaxLevels = 8;
+
+// Stage-1 kernel variant chosen for (x_dtype, d): team size, chunks per thread, rows in flight.
+struct Stage1Variant {
+    int xd, vec, team_size, k, rows;
+    const void *fn;
+    int block() const { return team_size < 256 ? 256 : team_size; }
+    int teams_per_block() const { return block() / team_size; }
+};
+
+// Returns nullptr if (x_dtype, d) is outside what the single-pass kernels cover.
+const Stage1Variant *select_stage1(int x_dtype, int64_t d);
+
+hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
+                                const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
+                                hipStream_t stream);
+hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, int num_slabs, float *G, int64_t d,
+                                hipStream_t stream);
+hipError_t launch_encode(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin, int num_sub,
+                         int L, int64_t d, hipStream_t stream);
+hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream);
+hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream);
+
+}  // namespace cr

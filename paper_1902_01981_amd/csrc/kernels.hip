@@ -1,0 +1,391 @@
+// HIP kernels of the CodedReduce hot path for gfx950 (64-wide wavefronts).  Everything here is HBM-bandwidth bound:
+// plain vector FMAs, 16-byte coalesced loads, no matrix cores.
+//
+//   partial_grads_kernel   CR.Execute step 1: G_piece = X[b:e]^T (phi(X[b:e] w) - y[b:e]) in ONE pass over the rows
+//   reduce_pieces_kernel   sums the pieces of each slab (fixed order, so results are reproducible bit for bit)
+//   encode_kernel          CR.Execute steps 2-5: every node's message, children folded into parents in registers
+//   decode_kernel          the master's decode  g = sum_j a_j m_(1,j)
+//   update_kernel          w <- w - lr g
+#include "kernels.h"
+
+#include <hip/hip_runtime.h>
+
+namespace cr {
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---- how a chunk of a row of X is fetched and widened to fp32 -------------------------------------------------
+template <int XD, int VEC> struct Chunk;
+
+template <> struct Chunk<0, 4> {
+    using raw_t = float4;
+    static __device__ __forceinline__ raw_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const float4 *>(static_cast<const float *>(X) + e); }
+    static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
+};
+template <> struct Chunk<1, 8> {
+    using raw_t = uint4;     // eight bf16 values
+    static __device__ __forceinline__ raw_t zero() { return make_uint4(0u, 0u, 0u, 0u); }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(X) + e); }
+    static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
+    {
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+        v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+        v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+};
+template <> struct Chunk<0, 1> {
+    using raw_t = float;
+    static __device__ __forceinline__ raw_t zero() { return 0.f; }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const float *>(X)[e]; }
+    static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = r; }
+};
+template <> struct Chunk<1, 1> {
+    using raw_t = uint16_t;
+    static __device__ __forceinline__ raw_t zero() { return 0; }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const uint16_t *>(X)[e]; }
+    static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
+};
+
+template <int VEC> __device__ __forceinline__ void store_row(float *dst, const float (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4 *>(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dst[i] = v[i];
+    }
+}
+
+// ---- stage 1 ------------------------------------------------------------------------------------------------------
+// A team of TS threads owns whole rows: thread t holds chunks t, t+TS, ... (K of them, VEC columns each) of every row it
+// works on, so a row is fetched once, used for the dot product x.w, kept in registers, and used again for the rank-1 update
+// acc += (phi(x.w) - y) x.  R rows are in flight per step.  The dot is reduced inside the wavefront and, for teams of several
+// wavefronts, through LDS (double buffered: one barrier per step).  Each piece ends with one d-float store of the accumulators.
+template <int XD, int VEC, int TS, int K, int R>
+__global__ void __launch_bounds__((TS < 256 ? 256 : TS))
+partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
+                     const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
+                     float *__restrict__ partial, int64_t d, int nq, int logistic)
+{
+    using C = Chunk<XD, VEC>;
+    using raw_t = typename C::raw_t;
+    constexpr int BLOCK = TS < 256 ? 256 : TS;
+    constexpr int WAVES = TS / 64;
+    const int tl = threadIdx.x % TS;
+    const int team = blockIdx.x * (BLOCK / TS) + threadIdx.x / TS;
+    __shared__ float red[2][R][WAVES];
+    if (team >= num_teams) return;   // whole teams only; teams of several wavefronts span the block, so barriers stay uniform
+
+    float wv[K][VEC];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int q = tl + k * TS;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) wv[k][v] = (q < nq) ? w[static_cast<int64_t>(q) * VEC + v] : 0.f;
+    }
+
+    const int pb = team_piece_begin[team], pe = team_piece_begin[team + 1];
+    int buf = 0;
+    for (int p = pb; p < pe; ++p) {
+        const DevPiece pc = pieces[p];
+        float acc[K][VEC];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
+
+        for (int r0 = 0; r0 < pc.nrows; r0 += R) {
+            raw_t xr[R][K];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
+                const int64_t base = (pc.row_begin + rr) * d;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    const int q = tl + k * TS;
+                    xr[r][k] = (q < nq) ? C::load(X, base + static_cast<int64_t>(q) * VEC) : C::zero();
+                }
+            }
+            float pd[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float xv[VEC];
+                    C::widen(xr[r][k], xv);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], wv[k][v], s);
+                }
+                pd[r] = wave_sum(s);
+            }
+            if constexpr (WAVES > 1) {
+                const int wave = tl / 64;
+                if ((tl & 63) == 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) red[buf][r][wave] = pd[r];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int wv_i = 0; wv_i < WAVES; ++wv_i) s += red[buf][r][wv_i];
+                    pd[r] = s;
+                }
+                buf ^= 1;
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int rr = r0 + r;
+                const float yy = y[pc.row_begin + min(rr, pc.nrows - 1)];
+                const float z = pd[r];
+                const float ph = logistic ? 1.f / (1.f + __expf(-z)) : z;
+                const float res = (rr < pc.nrows) ? ph - yy : 0.f;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float xv[VEC];
+                    C::widen(xr[r][k], xv);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[k][v] = fmaf(res, xv[v], acc[k][v]);
+                }
+            }
+        }
+        float *out = partial + static_cast<int64_t>(p) * d;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int q = tl + k * TS;
+            if (q < nq) store_row<VEC>(out + static_cast<int64_t>(q) * VEC, acc[k]);
+        }
+    }
+}
+
+// ---- piece reduction ------------------------------------------------------------------------------------------------
+template <int VEC>
+__global__ void __launch_bounds__(256)
+reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restrict__ slab_piece_begin, float *__restrict__ G, int64_t d, int nq)
+{
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    if (q >= nq) return;
+    const int slab = blockIdx.y;
+    const int pb = slab_piece_begin[slab], pe = slab_piece_begin[slab + 1];
+    double acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
+    for (int p = pb; p < pe; ++p) {
+        const float *src = partial + static_cast<int64_t>(p) * d + static_cast<int64_t>(q) * VEC;
+        float xv[VEC];
+        if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4 *>(src); xv[0] = t.x; xv[1] = t.y; xv[2] = t.z; xv[3] = t.w; }
+        else xv[0] = src[0];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += static_cast<double>(xv[v]);
+    }
+    float out[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) out[v] = static_cast<float>(acc[v]);
+    store_row<VEC>(G + static_cast<int64_t>(slab) * d + static_cast<int64_t>(q) * VEC, out);
+}
+
+// ---- encode ---------------------------------------------------------------------------------------------------------
+// One thread owns VEC columns and runs the whole sub-tree of one level-1 node for them: a post-order list of terms
+// (own += coef * G[slab]) in which the last term of a node carries a "finish" record: message = own + pending[level], stored
+// (rounded to fp32, as a transmitted message would be) and folded into pending[level-1] with the parent's decode coefficient.
+// Child messages therefore never come back from HBM; every active slab is read once and every message written once.
+// Terms are fetched kEncodeUnroll at a time so that many loads are in flight; arithmetic is fp64.
+template <int VEC, int LT>
+__global__ void __launch_bounds__(256)
+encode_kernel(const float *__restrict__ G, float *__restrict__ M, const EncTerm *__restrict__ terms, const EncFin *__restrict__ fins,
+              const int32_t *__restrict__ sub_begin, int64_t d, int nq)
+{
+    constexpr int U = kEncodeUnroll;
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    if (q >= nq) return;
+    const int tb = sub_begin[blockIdx.y], te = sub_begin[blockIdx.y + 1];
+    const int64_t col = static_cast<int64_t>(q) * VEC;
+
+    double pend[LT + 1][VEC];
+#pragma unroll
+    for (int l = 0; l <= LT; ++l)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) pend[l][v] = 0.0;
+    double own[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) own[v] = 0.0;
+
+    for (int t = tb; t < te; t += U) {
+        float xv[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float *src = G + static_cast<int64_t>(terms[t + u].slab) * d + col;
+            if constexpr (VEC == 4) { const float4 f = *reinterpret_cast<const float4 *>(src); xv[u][0] = f.x; xv[u][1] = f.y; xv[u][2] = f.z; xv[u][3] = f.w; }
+            else xv[u][0] = src[0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const EncTerm tm = terms[t + u];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) own[v] = fma(tm.coef, static_cast<double>(xv[u][v]), own[v]);
+            if (tm.fin >= 0) {
+                const EncFin f = fins[tm.fin];
+                float out[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    double msg = own[v];
+#pragma unroll
+                    for (int l = 1; l < LT; ++l)               // only levels 1..L-1 ever collect children
+                        if (l == f.level) { msg += pend[l][v]; pend[l][v] = 0.0; }
+                    out[v] = static_cast<float>(msg);
+                    own[v] = 0.0;
+                }
+                store_row<VEC>(M + static_cast<int64_t>(f.row) * d + col, out);
+#pragma unroll
+                for (int l = 1; l < LT; ++l)
+                    if (l == f.level - 1) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) pend[l][v] = fma(f.acoef, static_cast<double>(out[v]), pend[l][v]);
+                    }
+            }
+        }
+    }
+}
+
+// ---- decode ---------------------------------------------------------------------------------------------------------
+template <int VEC>
+__global__ void __launch_bounds__(256)
+decode_kernel(const float *__restrict__ M, float *__restrict__ g, const DecTerm *__restrict__ terms, int nterms, int64_t d, int nq)
+{
+    const int q = blockIdx.x * 256 + threadIdx.x;
+    if (q >= nq) return;
+    const int64_t col = static_cast<int64_t>(q) * VEC;
+    double acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
+    for (int j = 0; j < nterms; ++j) {
+        const DecTerm tm = terms[j];
+        const float *src = M + static_cast<int64_t>(tm.row) * d + col;
+        float xv[VEC];
+        if constexpr (VEC == 4) { const float4 f = *reinterpret_cast<const float4 *>(src); xv[0] = f.x; xv[1] = f.y; xv[2] = f.z; xv[3] = f.w; }
+        else xv[0] = src[0];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = fma(tm.coef, static_cast<double>(xv[v]), acc[v]);
+    }
+    float out[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) out[v] = static_cast<float>(acc[v]);
+    store_row<VEC>(g + col, out);
+}
+
+__global__ void __launch_bounds__(256) update_kernel(float *__restrict__ w, const float *__restrict__ g, float lr, int64_t d)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < d) w[i] = fmaf(-lr, g[i], w[i]);
+}
+
+// ---- variant table for stage 1 --------------------------------------------------------------------------------------
+#define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
+// fp32 x4 / scalar chunks: 4 (1) registers per chunk
+#define CR_FAMILY_NARROW(XD, VEC)                                                                                   \
+    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 8), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 4),                \
+    CR_V(XD, VEC, 256, 2, 8), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 4), CR_V(XD, VEC, 256, 6, 3),            \
+    CR_V(XD, VEC, 256, 8, 2), CR_V(XD, VEC, 256, 10, 2), CR_V(XD, VEC, 256, 12, 2),                                    \
+    CR_V(XD, VEC, 1024, 4, 2), CR_V(XD, VEC, 1024, 5, 1), CR_V(XD, VEC, 1024, 6, 1)
+// bf16 x8 chunks widen to eight accumulators each, so a thread can hold half as many
+#define CR_FAMILY_WIDE(XD, VEC)                                                                                     \
+    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 8), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 2),                \
+    CR_V(XD, VEC, 256, 2, 4), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 2), CR_V(XD, VEC, 256, 6, 2),            \
+    CR_V(XD, VEC, 1024, 2, 2), CR_V(XD, VEC, 1024, 3, 1)
+
+const Stage1Variant kVariants[] = {CR_FAMILY_NARROW(0, 4), CR_FAMILY_WIDE(1, 8), CR_FAMILY_NARROW(0, 1), CR_FAMILY_NARROW(1, 1)};
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+const Stage1Variant *select_stage1(int x_dtype, int64_t d)
+{
+    const int wide = (x_dtype == 1) ? 8 : 4;
+    const int vec = (d % wide == 0) ? wide : 1;
+    const int64_t nq = d / vec;
+    const Stage1Variant *best = nullptr;
+    for (const Stage1Variant &v : kVariants) {
+        if (v.xd != x_dtype || v.vec != vec) continue;
+        if (static_cast<int64_t>(v.team_size) * v.k < nq) continue;
+        // smallest team that covers the row, then the fewest chunks per thread
+        if (!best || v.team_size < best->team_size || (v.team_size == best->team_size && v.k < best->k)) best = &v;
+    }
+    return best;
+}
+
+hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
+                                const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
+                                hipStream_t stream)
+{
+    int nq = static_cast<int>(d / v.vec);
+    void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &d, &nq, &logistic};
+    const int tpb = v.teams_per_block();
+    dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
+    return hipLaunchKernel(v.fn, grid, block, args, 0, stream);
+}
+
+hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, int num_slabs, float *G, int64_t d, hipStream_t stream)
+{
+    if (d % 4 == 0) {
+        const int nq = static_cast<int>(d / 4);
+        reduce_pieces_kernel<4><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, G, d, nq);
+    } else {
+        const int nq = static_cast<int>(d);
+        reduce_pieces_kernel<1><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, G, d, nq);
+    }
+    return hipGetLastError();
+}
+
+template <int VEC>
+static hipError_t launch_encode_vec(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin,
+                                    int num_sub, int L, int64_t d, hipStream_t stream)
+{
+    const int nq = static_cast<int>(d / VEC);
+    const dim3 grid((nq + 255) / 256, num_sub), block(256);
+    if (L <= 1) encode_kernel<VEC, 1><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    else if (L == 2) encode_kernel<VEC, 2><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    else if (L == 3) encode_kernel<VEC, 3><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    else if (L == 4) encode_kernel<VEC, 4><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    else encode_kernel<VEC, kMaxLevels><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin, int num_sub,
+                         int L, int64_t d, hipStream_t stream)
+{
+    if (d % 4 == 0 && aligned16(G) && aligned16(M)) return launch_encode_vec<4>(G, M, terms, fins, sub_begin, num_sub, L, d, stream);
+    return launch_encode_vec<1>(G, M, terms, fins, sub_begin, num_sub, L, d, stream);
+}
+
+hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream)
+{
+    if (d % 4 == 0 && aligned16(M) && aligned16(g)) {
+        const int nq = static_cast<int>(d / 4);
+        decode_kernel<4><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq);
+    } else {
+        const int nq = static_cast<int>(d);
+        decode_kernel<1><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream)
+{
+    update_kernel<<<static_cast<unsigned>((d + 255) / 256), 256, 0, stream>>>(w, g, lr, d);
+    return hipGetLastError();
+}
+
+}  // namespace cr

@@ -1,0 +1,227 @@
+"""HIP path vs oracle, element by element, on seeded inputs that span several tiles and ragged tails.
+Bars: relative L2 <= 1e-4 (fp32 X) or 5e-3 (bf16 X) for the decoded gradient, every slab and every message."""
+import numpy as np
+import pytest
+
+import paper_1902_01981_amd as cr
+from cr_inputs import workloads as wl
+from _harness import TOL, HipPath, OraclePath, rel_l2
+
+pytestmark = pytest.mark.gpu
+B_PRINTED = np.array([[0.5, 1, 0], [0, 1, -1], [0.5, 0, 1]])
+
+
+def _torch():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def _check_iteration(hip, orc, w, mask, tol, check_rows=True):
+    torch = _torch()
+    w_dev = torch.from_numpy(w).cuda()
+    g = hip.gradient(w_dev, mask)
+    sg = orc.slab_grads(w)
+    ng = orc.node_grads(sg)
+    msgs, g_cr = orc.execute(ng, mask)
+    gstar = orc.full_gradient(w)
+    assert rel_l2(g_cr, gstar) < 1e-9                    # the oracle's tree result is the plain definition
+    assert rel_l2(g, gstar) <= tol, ("decoded gradient", rel_l2(g, gstar))
+    if check_rows:
+        G = hip.ws.slab_grads().cpu().numpy()
+        for q, ref in enumerate(sg):
+            assert rel_l2(G[q], ref) <= tol, ("slab", q, rel_l2(G[q], ref))
+        M = hip.ws.messages().cpu().numpy()
+        for node, ref in enumerate(msgs):
+            if ref is not None:
+                assert rel_l2(M[node], ref) <= tol, ("message", node, rel_l2(M[node], ref))
+    return g
+
+
+def test_cfg1_every_mask():
+    """Tiny tree (L=2, n=3, s=1), 1200 x 100 linear regression: all 256 masks with at most one straggler per group."""
+    torch = _torch()
+    cfg = wl.config("cfg1")
+    data = wl.make_dataset(cfg)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR)
+    assert hip.info.num_slabs == 27 and hip.info.row_visits == 3840
+    w = data["w0"]
+    w_dev = torch.from_numpy(w).cuda()
+    sg = orc.slab_grads(w)
+    ng = orc.node_grads(sg)
+    gstar = orc.full_gradient(w)
+    count = 0
+    for mask in wl.enumerate_masks(cfg["L"], cfg["n"], cfg["s"]):
+        g = hip.gradient(w_dev, mask)
+        assert rel_l2(g, gstar) <= 1e-4, (mask, rel_l2(g, gstar))
+        if count % 16 == 0:
+            msgs, _ = orc.execute(ng, mask)
+            M = hip.ws.messages().cpu().numpy()
+            for node, ref in enumerate(msgs):
+                if ref is not None:
+                    assert rel_l2(M[node], ref) <= 1e-4
+        count += 1
+    assert count == 256
+    G = hip.ws.slab_grads().cpu().numpy()
+    for q, ref in enumerate(sg):
+        assert rel_l2(G[q], ref) <= 1e-4
+    hip.close()
+
+
+def test_printed_code_of_the_example():
+    """The (3,2) example with the printed B: messages are the printed combinations of partition gradients."""
+    cfg = wl.config("cfg1", m=1500, d=52)
+    data = wl.make_dataset(cfg)
+    hip = HipPath(2, 3, 1, data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32, B=B_PRINTED)
+    orc = OraclePath(2, 3, 1, data["X"], data["y"], cr.CR_LINEAR, B=B_PRINTED)
+    mask = np.zeros(12, dtype=np.uint8)
+    mask[[1, 5]] = 1
+    g = _check_iteration(hip, orc, data["w0"], mask, 1e-4)
+    gD = [orc.seg_grad(data["w0"], 500 * k, 500 * (k + 1)) for k in range(3)]
+    M = hip.ws.messages().cpu().numpy()
+    assert rel_l2(M[0], 0.5 * gD[0] + gD[1]) <= 1e-4 and rel_l2(M[2], 0.5 * gD[0] + gD[2]) <= 1e-4
+    assert rel_l2(g, gD[0] + gD[1] + gD[2]) <= 1e-4
+    hip.close()
+
+
+CASES = [
+    # name, L, n, s, m, d, model, x_dtype, teams
+    ("cfg2-shape", 2, 4, 1, 6_007, 10_000, cr.CR_LINEAR, cr.CR_F32, None),       # 256-thread teams, 10 chunks per thread, ragged last chunk
+    ("cfg2-few-teams", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, 37),      # pieces crossing slab boundaries
+    ("cfg3-shape", 3, 4, 1, 8_400, 4_096, cr.CR_LOGISTIC, cr.CR_F32, None),
+    ("cfg5-shape", 3, 6, 2, 25_801, 1_024, cr.CR_LINEAR, cr.CR_BF16, None),       # one wavefront per row, bf16 x8 chunks
+    ("bf16-wide", 2, 3, 1, 2_000, 8_192, cr.CR_LOGISTIC, cr.CR_BF16, None),       # bf16 with 256-thread teams
+    ("odd-d-fp32", 2, 3, 1, 1_111, 1_003, cr.CR_LINEAR, cr.CR_F32, None),         # d % 4 != 0: scalar chunks everywhere
+    ("odd-d-bf16", 2, 3, 1, 1_111, 270, cr.CR_LINEAR, cr.CR_BF16, None),
+    ("tiny-d", 1, 5, 2, 333, 4, cr.CR_LINEAR, cr.CR_F32, None),                   # one layer: master-worker gradient coding
+    ("s0-plain-tree", 2, 4, 0, 4_000, 256, cr.CR_LINEAR, cr.CR_F32, None),
+    ("deep", 4, 2, 1, 3_000, 520, cr.CR_LOGISTIC, cr.CR_F32, None),
+    ("big-team", 2, 3, 1, 700, 16_384, cr.CR_LINEAR, cr.CR_F32, None),            # 1024-thread teams
+    ("m-equals-N", 2, 3, 1, 12, 64, cr.CR_LINEAR, cr.CR_F32, None),               # one row per worker
+]
+
+
+@pytest.mark.parametrize("name,L,n,s,m,d,model,x_dtype,teams", CASES, ids=[c[0] for c in CASES])
+def test_shapes_and_kernel_variants(name, L, n, s, m, d, model, x_dtype, teams):
+    base = "cfg3" if model == cr.CR_LOGISTIC else ("cfg5" if x_dtype == cr.CR_BF16 else "cfg2")
+    cfg = wl.config(base, L=L, n=n, s=s, m=m, d=d, model=model, x_dtype=x_dtype, w0_std=None if model == cr.CR_LOGISTIC else 1.0)
+    data = wl.make_dataset(cfg)
+    hip = HipPath(L, n, s, data["X"], data["y"], model, x_dtype, teams=teams)
+    orc = OraclePath(L, n, s, data["X"], data["y"], model)
+    rng = wl.mask_stream(cfg)
+    N = wl.num_workers(n, L)
+    masks = [np.zeros(N, dtype=np.uint8)] + [wl.draw_mask(rng, L, n, s) for _ in range(3)]
+    for mask in masks:
+        _check_iteration(hip, orc, data["w0"], mask, TOL[x_dtype])
+    hip.close()
+
+
+def test_gd_trajectory_cfg1():
+    """Gradient descent with a fresh mask per step: the HIP path is fed its own w; the oracle is given the same w each step."""
+    torch = _torch()
+    cfg = wl.config("cfg1")
+    data = wl.make_dataset(cfg)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR)
+    rng = wl.mask_stream(cfg)
+    w_dev = torch.from_numpy(data["w0"]).cuda()
+    ner = []
+    for step in range(10):
+        mask = wl.draw_mask(rng, cfg["L"], cfg["n"], cfg["s"])
+        w_host = w_dev.cpu().numpy()
+        g = hip.gradient(w_dev, mask)
+        assert rel_l2(g, orc.full_gradient(w_host)) <= 1e-4
+        cr.cr_gd_update(hip.plan, w_dev, hip.g, 2e-4)
+        cr.cr_synchronize(hip.plan)
+        np.testing.assert_allclose(w_dev.cpu().numpy(), w_host - np.float32(2e-4) * g, rtol=1e-6, atol=1e-7)
+        ner.append(float(np.sum((w_dev.cpu().numpy() - data["w_star"]) ** 2) / np.sum(data["w_star"] ** 2)))
+    assert all(b < a for a, b in zip(ner, ner[1:]))
+    hip.close()
+
+
+def test_aggregation_only():
+    """Partition gradients supplied as vectors (L=2, n=8, s=2): encode + decode alone, 20 masks."""
+    torch = _torch()
+    L, n, s, d = 2, 8, 2, 70_004                        # several 1024-column blocks and a ragged one
+    cfg = wl.config("cfg4", d=d)
+    plan = cr.cr_plan_ex(L, n, s, cfg["m"], d, model=cr.CR_AGGREGATE_ONLY)
+    ws = cr.Workspace(plan)
+    assert ws.info.num_slabs == 248 and ws.info.num_workers == 72
+    orc = OraclePath(L, n, s, np.zeros((cfg["m"], 1), dtype=np.float32), np.zeros(cfg["m"], dtype=np.float32), cr.CR_LINEAR)
+    rb = [b for (_, b, _, _) in orc.slabs]
+    re_ = [e for (_, _, e, _) in orc.slabs]
+    cuts, member = wl.atoms_of(rb, re_)
+    assert len(cuts) - 1 == 56
+    atoms = wl.atom_vectors(cfg["seed"], len(cuts) - 1, 0, d)
+    G = np.stack([atoms[idx].sum(axis=0, dtype=np.float32) for idx in member])   # redundant copies of a row range agree
+    G_dev = torch.from_numpy(G).cuda()
+    g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
+    slab_grads = [G[q].astype(np.float64) for q in range(len(member))]
+    ng = []
+    for node in range(72):
+        acc = np.zeros(d)
+        for q, (nd, _, _, c) in enumerate(orc.slabs):
+            if nd == node:
+                acc += float(c) * slab_grads[q]
+        ng.append(acc)
+    rng = wl.mask_stream(cfg)
+    for trial in range(20):
+        mask = wl.draw_mask(rng, L, n, s)
+        cr.cr_load_partial_grads(plan, G_dev)
+        cr.cr_encode_tree(plan, mask)
+        cr.cr_decode_root(plan, g_dev)
+        cr.cr_synchronize(plan)
+        msgs, g_ref = orc.execute(ng, mask)
+        assert rel_l2(g_dev.cpu().numpy(), g_ref) <= 1e-4, (trial, rel_l2(g_dev.cpu().numpy(), g_ref))
+        if trial % 5 == 0:
+            M = ws.messages().cpu().numpy()
+            for node, ref in enumerate(msgs):
+                if ref is not None:
+                    assert rel_l2(M[node], ref) <= 1e-4
+    # the decoded vector is the sum of all atoms, whatever the mask
+    assert rel_l2(g_dev.cpu().numpy(), atoms.astype(np.float64).sum(0)) <= 1e-4
+    cr.cr_plan_destroy(plan)
+
+
+def test_failure_paths_leave_state_alone():
+    torch = _torch()
+    cfg = wl.config("cfg1")
+    data = wl.make_dataset(cfg)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    w_dev = torch.from_numpy(data["w0"]).cuda()
+    lib = cr.load_library()
+    ok = np.zeros(12, dtype=np.uint8)
+    with pytest.raises(cr.CodedReduceError) as ei:       # encode before any gradients
+        cr.cr_encode_tree(hip.plan, ok)
+    assert ei.value.status == cr.CR_E_STATE
+    g_ok = hip.gradient(w_dev, ok).copy()
+    M_before = hip.ws.messages().cpu().numpy().copy()
+    bad = ok.copy()
+    bad[[3, 4]] = 1                                      # two stragglers among the children of node (1,1)
+    with pytest.raises(cr.CodedReduceError) as ei:
+        cr.cr_encode_tree(hip.plan, bad)
+    assert ei.value.status == cr.CR_E_UNDECODABLE
+    cr.cr_decode_root(hip.plan, hip.g)                   # the previous messages are still in place
+    cr.cr_synchronize(hip.plan)
+    assert np.array_equal(hip.g.cpu().numpy(), g_ok) and np.array_equal(hip.ws.messages().cpu().numpy(), M_before)
+    cr.cr_partial_grads(hip.plan, hip.X, hip.y, w_dev)
+    with pytest.raises(cr.CodedReduceError) as ei:       # decode before the new encode
+        cr.cr_decode_root(hip.plan, hip.g)
+    assert ei.value.status == cr.CR_E_STATE
+    assert lib.cr_partial_grads(hip.plan, hip.X.data_ptr() + 4, hip.y.data_ptr(), w_dev.data_ptr()) == cr.CR_E_INVAL
+    hip.close()
+
+
+def test_repeat_runs_are_bit_identical():
+    torch = _torch()
+    cfg = wl.config("cfg2", m=4_000, d=2_048)
+    data = wl.make_dataset(cfg)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    w_dev = torch.from_numpy(data["w0"]).cuda()
+    mask = wl.draw_mask(wl.mask_stream(cfg), cfg["L"], cfg["n"], cfg["s"])
+    a = hip.gradient(w_dev, mask).copy()
+    b = hip.gradient(w_dev, mask).copy()
+    assert np.array_equal(a, b)                          # fixed reduction order, no floating-point atomics
+    hip.close()
