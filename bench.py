@@ -87,7 +87,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle work for the CPU baseline (0 = skip)")
-    ap.add_argument("--teams", type=int, default=0, help="override the stage-1 work split")
+    ap.add_argument("--teams", type=int, default=0, help="stage-1 split: this many equal contiguous ranges")
+    ap.add_argument("--cell-rows", type=int, default=0, help="stage-1 split: row cells of this many rows")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain 1 GiB elementwise copy kernel a few times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -118,7 +119,9 @@ def main() -> int:
     t0 = time.perf_counter()
     plan = cr.cr_plan_ex(L, n, s, m, d, model=cfg["model"], x_dtype=cfg["x_dtype"])
     if args.teams and not aggregate:
-        cr.cr_plan_set_teams(plan, args.teams)
+        cr.cr_plan_set_split(plan, cr.CR_SPLIT_EQUAL_RANGES, args.teams)
+    elif args.cell_rows and not aggregate:
+        cr.cr_plan_set_split(plan, cr.CR_SPLIT_ROW_CELLS, args.cell_rows)
 
     # ---- inputs, generated on the host from the seed and moved to HBM before any timing
     data = None

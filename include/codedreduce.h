@@ -66,7 +66,7 @@ typedef struct cr_plan_info {
     int32_t num_slabs;       /* S: (worker, segment) pairs; one d-float partial gradient each */
     int32_t num_decode_rows; /* F = C(n,s) */
     int32_t code_candidate;  /* index of the winning candidate of the code search, -1 if B was supplied */
-    int32_t num_teams;       /* stage-1 work split (0 until known, see cr_plan_set_teams) */
+    int32_t num_teams;       /* stage-1 work split (0 until known, see cr_plan_set_split) */
     int32_t num_pieces;      /* stage-1 partial rows (0 until the split is known) */
     int64_t m, d;
     int64_t row_visits;      /* sum over workers of allocated rows */
@@ -99,15 +99,20 @@ int cr_plan_get_slabs(const cr_plan_t *plan, int32_t *node, int64_t *row_begin, 
 /* decode row for one sibling group (Section III-A, CR.Execute step 3): flags[j] != 0 marks child j a straggler.  With fewer than
  * s stragglers the set is padded with the highest-index survivors.  a: host, n doubles.  CR_E_UNDECODABLE if more than s are set. */
 int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */, double *a);
-/* Stage-1 work split: the row visits of all slabs, slab-major, are cut into `teams` equal contiguous ranges; a range that crosses a
- * slab boundary is cut there, giving the pieces.  Chosen from the device at cr_workspace_bytes unless set here first (teams >= 1). */
-int cr_plan_set_teams(cr_plan_t *plan, int teams);
-int cr_plan_get_pieces(const cr_plan_t *plan, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team); /* num_pieces entries each */
+/* Stage-1 work split into pieces (a piece = a run of one slab's rows handled by one team; it owns one d-float partial row).
+ *   CR_SPLIT_EQUAL_RANGES  value = teams: the row visits of all slabs, slab-major, are cut into `teams` equal contiguous ranges,
+ *                          cut again at slab boundaries.
+ *   CR_SPLIT_ROW_CELLS     value = rows per cell: every slab is cut on one global grid of that many rows, one piece per team, teams
+ *                          ordered by cell so that the holders of the same rows run at the same time.
+ * Default (when this is never called): row cells of about 4 MB of X.  CR_E_STATE once a workspace is bound. */
+enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1 };
+int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
+/* pieces in execution order: piece i is rows [row_begin[i], row_end[i]) of slab[i], run by team[i]; num_pieces entries each, any may be NULL */
+int cr_plan_get_pieces(const cr_plan_t *plan, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team);
 
 /* ---- device binding --------------------------------------------------------------------------------------------
  * The workspace holds the device tables, the per-call encode program, the stage-1 piece partials, the slab gradients
- * G[S][d] (not for CR_AGGREGATE_ONLY) and the messages M[N][d], all fp32 rows of d floats.  cr_workspace_bytes needs a
- * current HIP device unless cr_plan_set_teams was called.  dev_ptr must be 256-byte aligned and stay valid while the plan
+ * G[S][d] (not for CR_AGGREGATE_ONLY) and the messages M[N][d], all fp32 rows of d floats.  dev_ptr must be 256-byte aligned and stay valid while the plan
  * is used; hip_stream is a hipStream_t (NULL = the default stream).  cr_bind_workspace copies the tables synchronously. */
 int cr_workspace_bytes(cr_plan_t *plan, size_t *bytes);
 int cr_bind_workspace(cr_plan_t *plan, void *dev_ptr, size_t bytes, void *hip_stream);

@@ -19,11 +19,12 @@ CR_OK, CR_E_INVAL, CR_E_UNDECODABLE, CR_E_STATE, CR_E_HIP, CR_E_NOMEM = 0, -1, -
 CR_LINEAR, CR_LOGISTIC, CR_AGGREGATE_ONLY = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
 CR_K_PARTIAL_GRADS, CR_K_REDUCE_PIECES, CR_K_ENCODE, CR_K_DECODE, CR_K_UPDATE, CR_K_COUNT = 0, 1, 2, 3, 4, 5
+CR_SPLIT_EQUAL_RANGES, CR_SPLIT_ROW_CELLS = 0, 1
 DEFAULT_SEED = 190201981
 
 EXPORTS = [
     "cr_plan", "cr_plan_ex", "cr_plan_destroy", "cr_plan_info", "cr_plan_get_B", "cr_plan_get_A", "cr_plan_get_slabs",
-    "cr_plan_decode_row", "cr_plan_set_teams", "cr_plan_get_pieces", "cr_workspace_bytes", "cr_bind_workspace",
+    "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
 ]
@@ -63,7 +64,7 @@ def load_library():
         lib.cr_plan_get_A.argtypes = [vp, vp]
         lib.cr_plan_get_slabs.argtypes = [vp, vp, vp, vp, vp]
         lib.cr_plan_decode_row.argtypes = [vp, vp, vp]
-        lib.cr_plan_set_teams.argtypes = [vp, c_int]
+        lib.cr_plan_set_split.argtypes = [vp, c_int, i64]
         lib.cr_plan_get_pieces.argtypes = [vp, vp, vp, vp, vp]
         lib.cr_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         lib.cr_bind_workspace.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -162,8 +163,8 @@ def cr_plan_decode_row(plan: int, flags) -> np.ndarray:
     return a
 
 
-def cr_plan_set_teams(plan: int, teams: int) -> None:
-    _check(load_library().cr_plan_set_teams(plan, teams))
+def cr_plan_set_split(plan: int, kind: int, value: int) -> None:
+    _check(load_library().cr_plan_set_split(plan, kind, value))
 
 
 def cr_plan_get_pieces(plan: int):

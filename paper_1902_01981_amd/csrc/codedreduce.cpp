@@ -64,9 +64,9 @@ struct cr_plan_s {
 
     // stage-1 split
     const cr::Stage1Variant *variant = nullptr;
-    int teams = 0;
-    std::vector<cr::Piece> pieces;
-    std::vector<int32_t> slab_piece_begin, team_piece_begin;
+    int split_kind = -1;                            // -1: choose from the device when the workspace is sized
+    int64_t split_value = 0;
+    cr::Split split;
 
     // device binding
     bool bound = false;
@@ -74,7 +74,7 @@ struct cr_plan_s {
     char *ws = nullptr;
     size_t ws_bytes = 0;
     cr::DevPiece *d_pieces = nullptr;
-    int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr;
+    int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr, *d_slab_pieces = nullptr;
     char *d_program = nullptr;                     // per-call encode program + root decode terms
     size_t program_bytes = 0;
     float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr;
@@ -84,8 +84,8 @@ struct cr_plan_s {
     bool staging_used[kStagingSlots] = {};
     int staging_next = 0;
     // layout of the program block (offsets in bytes, fixed per plan)
-    size_t off_terms = 0, off_fins = 0, off_sub = 0, off_dec = 0;
-    size_t max_terms = 0, max_fins = 0;
+    size_t off_slab = 0, off_level = 0, off_row = 0, off_coef = 0, off_acoef = 0, off_sub = 0, off_dec = 0;
+    size_t max_terms = 0;
     int num_dec_terms = 0;
 
     bool have_grads = false, have_messages = false;
@@ -122,44 +122,52 @@ int group_decode_row(const cr_plan_t *p, const uint8_t *flags, const double **ro
     return CR_OK;
 }
 
+// MI355X has 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin by workgroup id.
+constexpr int kL2Domains = 8;
+
 int ensure_split(cr_plan_t *p)
 {
-    if (!p->pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
+    if (!p->split.pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
     if (!p->variant) return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels");
-    if (p->teams <= 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        CR_HIP(hipGetDevice(&dev));
-        CR_HIP(hipGetDeviceProperties(&prop, dev));
-        int per_cu = 0;
-        CR_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn, p->variant->block(), 0));
-        if (per_cu < 1) per_cu = 1;
-        int oversub = 1;
-        if (const char *e = std::getenv("CR_STAGE1_OVERSUB")) oversub = std::max(1, std::atoi(e));
-        int64_t teams = static_cast<int64_t>(prop.multiProcessorCount) * per_cu * p->variant->teams_per_block() * oversub;
-        p->teams = static_cast<int>(std::min<int64_t>(teams, std::max<int64_t>(1, p->row_visits)));
+    int kind = p->split_kind;
+    int64_t value = p->split_value;
+    if (kind < 0) {
+        // default: row cells of about 4 MB of X, a multiple of 32 rows.  Long enough that the d-float partial row each piece
+        // writes is a fraction of a percent of what it reads, short enough that the last cells do not leave the chip half empty.
+        kind = CR_SPLIT_ROW_CELLS;
+        const int64_t row_bytes = p->d * elem_size(p);
+        value = std::min<int64_t>(4096, std::max<int64_t>(32, ((int64_t(4) << 20) / row_bytes + 16) / 32 * 32));
     }
-    cr::split_pieces(p->slabs, p->teams, p->pieces, p->slab_piece_begin, p->team_piece_begin);
+    if (kind == CR_SPLIT_ROW_CELLS) {
+        if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
+        cr::split_row_cells(p->slabs, value, kL2Domains, p->variant->teams_per_block(), p->split);
+    } else {
+        const int teams = static_cast<int>(std::min<int64_t>(value, std::max<int64_t>(1, p->row_visits)));
+        cr::split_equal_ranges(p->slabs, teams, p->split);
+    }
     return CR_OK;
 }
 
 void compute_layout(cr_plan_t *p, size_t *total)
 {
-    const size_t S = p->slabs.size(), N = p->tree.N, P = p->pieces.size();
+    const size_t S = p->slabs.size(), N = p->tree.N, P = p->split.pieces.size();
     // worst case: one term per slab plus one dummy per node, each sub-program padded to the unroll
-    p->max_terms = S + N + static_cast<size_t>(p->n) * cr::kEncodeUnroll;
-    p->max_fins = N;
+    p->max_terms = align_up(S + N + static_cast<size_t>(p->n) * cr::kEncodeUnroll, cr::kEncodeUnroll);
     size_t off = 0;
-    p->off_terms = off; off = align_up(off + p->max_terms * sizeof(cr::EncTerm), 256);
-    p->off_fins = off;  off = align_up(off + p->max_fins * sizeof(cr::EncFin), 256);
+    p->off_slab = off;  off = align_up(off + p->max_terms * sizeof(int32_t), 256);
+    p->off_level = off; off = align_up(off + p->max_terms * sizeof(int32_t), 256);
+    p->off_row = off;   off = align_up(off + p->max_terms * sizeof(int32_t), 256);
+    p->off_coef = off;  off = align_up(off + p->max_terms * sizeof(double), 256);
+    p->off_acoef = off; off = align_up(off + p->max_terms * sizeof(double), 256);
     p->off_sub = off;   off = align_up(off + (p->n + 1) * sizeof(int32_t), 256);
     p->off_dec = off;   off = align_up(off + p->n * sizeof(cr::DecTerm), 256);
     p->program_bytes = off;
 
     size_t w = 0;
     w = align_up(w + P * sizeof(cr::DevPiece), 256);
-    w = align_up(w + (p->teams + 1) * sizeof(int32_t), 256);
+    w = align_up(w + (p->split.teams + 1) * sizeof(int32_t), 256);
     w = align_up(w + (S + 1) * sizeof(int32_t), 256);
+    w = align_up(w + P * sizeof(int32_t), 256);
     w = align_up(w + p->program_bytes, 256);
     const size_t row = static_cast<size_t>(p->d) * sizeof(float);
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -295,8 +303,8 @@ int cr_plan_info(const cr_plan_t *p, cr_plan_info_t *info)
     info->num_slabs = static_cast<int32_t>(p->slabs.size());
     info->num_decode_rows = static_cast<int32_t>(cr::num_straggler_sets(p->n, p->s, int64_t(1) << 20));
     info->code_candidate = p->code.candidate;
-    info->num_teams = p->pieces.empty() ? 0 : p->teams;
-    info->num_pieces = static_cast<int32_t>(p->pieces.size());
+    info->num_teams = p->split.teams;
+    info->num_pieces = static_cast<int32_t>(p->split.pieces.size());
     info->m = p->m; info->d = p->d;
     info->row_visits = p->row_visits;
     info->min_rows = p->min_rows; info->max_rows = p->max_rows;
@@ -347,24 +355,28 @@ int cr_plan_decode_row(const cr_plan_t *p, const uint8_t *flags, double *a)
     return CR_OK;
 }
 
-int cr_plan_set_teams(cr_plan_t *p, int teams)
+int cr_plan_set_split(cr_plan_t *p, int kind, int64_t value)
 {
-    if (!p || teams < 1) return fail(CR_E_INVAL, "teams must be >= 1");
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    if (kind != CR_SPLIT_EQUAL_RANGES && kind != CR_SPLIT_ROW_CELLS) return fail(CR_E_INVAL, "unknown split kind");
+    if (value < 1) return fail(CR_E_INVAL, "split value must be >= 1");
+    if (kind == CR_SPLIT_EQUAL_RANGES && value > (int64_t(1) << 24)) return fail(CR_E_INVAL, "too many teams");
     if (p->bound) return fail(CR_E_STATE, "the work split cannot change once a workspace is bound");
     if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_INVAL, "an aggregation-only plan has no stage-1 split");
-    p->teams = static_cast<int>(std::min<int64_t>(teams, p->row_visits));
-    p->pieces.clear();
+    p->split_kind = kind;
+    p->split_value = value;
+    p->split = cr::Split();
     return ensure_split(p);
 }
 
 int cr_plan_get_pieces(const cr_plan_t *p, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team)
 {
     if (!p) return fail(CR_E_INVAL, "NULL plan");
-    for (size_t i = 0; i < p->pieces.size(); ++i) {
-        if (slab) slab[i] = p->pieces[i].slab;
-        if (row_begin) row_begin[i] = p->pieces[i].row_begin;
-        if (row_end) row_end[i] = p->pieces[i].row_end;
-        if (team) team[i] = p->pieces[i].team;
+    for (size_t i = 0; i < p->split.pieces.size(); ++i) {
+        if (slab) slab[i] = p->split.pieces[i].slab;
+        if (row_begin) row_begin[i] = p->split.pieces[i].row_begin;
+        if (row_end) row_end[i] = p->split.pieces[i].row_end;
+        if (team) team[i] = p->split.pieces[i].team;
     }
     return CR_OK;
 }
@@ -392,12 +404,13 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     p->ws = static_cast<char *>(dev_ptr);
     p->ws_bytes = bytes;
 
-    const size_t S = p->slabs.size(), N = p->tree.N, P = p->pieces.size();
+    const size_t S = p->slabs.size(), N = p->tree.N, P = p->split.pieces.size();
     const size_t row = static_cast<size_t>(p->d) * sizeof(float);
     size_t w = 0;
     p->d_pieces = reinterpret_cast<cr::DevPiece *>(p->ws + w);             w = align_up(w + P * sizeof(cr::DevPiece), 256);
-    p->d_team_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (p->teams + 1) * sizeof(int32_t), 256);
+    p->d_team_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (p->split.teams + 1) * sizeof(int32_t), 256);
     p->d_slab_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (S + 1) * sizeof(int32_t), 256);
+    p->d_slab_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + P * sizeof(int32_t), 256);
     p->d_program = p->ws + w;                                              w = align_up(w + p->program_bytes, 256);
     p->d_partial = nullptr; p->d_G = nullptr;
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -410,10 +423,11 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     if (P > 0) {
         std::vector<cr::DevPiece> hp(P);
         for (size_t i = 0; i < P; ++i)
-            hp[i] = {p->pieces[i].row_begin, static_cast<int32_t>(p->pieces[i].row_end - p->pieces[i].row_begin), p->pieces[i].slab};
+            hp[i] = {p->split.pieces[i].row_begin, static_cast<int32_t>(p->split.pieces[i].row_end - p->split.pieces[i].row_begin), p->split.pieces[i].slab};
         CR_HIP(hipMemcpy(p->d_pieces, hp.data(), P * sizeof(cr::DevPiece), hipMemcpyHostToDevice));
-        CR_HIP(hipMemcpy(p->d_team_piece_begin, p->team_piece_begin.data(), (p->teams + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
-        CR_HIP(hipMemcpy(p->d_slab_piece_begin, p->slab_piece_begin.data(), (S + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+        CR_HIP(hipMemcpy(p->d_team_piece_begin, p->split.team_piece_begin.data(), (p->split.teams + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+        CR_HIP(hipMemcpy(p->d_slab_piece_begin, p->split.slab_piece_begin.data(), (S + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+        CR_HIP(hipMemcpy(p->d_slab_pieces, p->split.slab_pieces.data(), P * sizeof(int32_t), hipMemcpyHostToDevice));
     }
     if (!p->h_staging) {
         CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kStagingSlots, hipHostMallocDefault));
@@ -431,17 +445,18 @@ int cr_partial_grads(cr_plan_t *p, const void *X, const float *y, const float *w
     if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
     if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_STATE, "aggregation-only plan: use cr_load_partial_grads");
     if (reinterpret_cast<uintptr_t>(X) % 16 != 0) return fail(CR_E_INVAL, "X must be 16-byte aligned");
-    const int64_t S = static_cast<int64_t>(p->slabs.size()), P = static_cast<int64_t>(p->pieces.size());
+    const int64_t S = static_cast<int64_t>(p->slabs.size()), P = static_cast<int64_t>(p->split.pieces.size());
     {
-        const int64_t bytes = p->row_visits * p->d * elem_size(p) + p->row_visits * 4 + P * p->d * 4 + p->d * 4;
+        // what the method must move: every holder reads its rows and targets once, each slab gradient is written once
+        const int64_t bytes = p->row_visits * p->d * elem_size(p) + p->row_visits * 4 + S * p->d * 4 + p->d * 4;
         LaunchTimer t(p, CR_K_PARTIAL_GRADS, bytes);
-        CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->teams, p->d_partial, p->d,
+        CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->split.teams, p->d_partial, p->d,
                                         p->model == CR_LOGISTIC ? 1 : 0, p->stream));
         t.done();
     }
     {
         LaunchTimer t(p, CR_K_REDUCE_PIECES, (P + S) * p->d * 4);
-        CR_HIP(cr::launch_reduce_pieces(p->d_partial, p->d_slab_piece_begin, static_cast<int>(S), p->d_G, p->d, p->stream));
+        CR_HIP(cr::launch_reduce_pieces(p->d_partial, p->d_slab_piece_begin, p->d_slab_pieces, static_cast<int>(S), p->d_G, p->d, p->stream));
         t.done();
     }
     p->G_src = p->d_G;
@@ -482,13 +497,17 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     p->staging_next = (slot + 1) % kStagingSlots;
     if (p->staging_used[slot]) CR_HIP(hipEventSynchronize(p->staging_done[slot]));
     char *h = p->h_staging + static_cast<size_t>(slot) * p->program_bytes;
-    cr::EncTerm *terms = reinterpret_cast<cr::EncTerm *>(h + p->off_terms);
-    cr::EncFin *fins = reinterpret_cast<cr::EncFin *>(h + p->off_fins);
+    int32_t *t_slab = reinterpret_cast<int32_t *>(h + p->off_slab);
+    int32_t *t_level = reinterpret_cast<int32_t *>(h + p->off_level);
+    int32_t *t_row = reinterpret_cast<int32_t *>(h + p->off_row);
+    double *t_coef = reinterpret_cast<double *>(h + p->off_coef);
+    double *t_acoef = reinterpret_cast<double *>(h + p->off_acoef);
+    auto put = [&](size_t t, int32_t slab, double coef) { t_slab[t] = slab; t_level[t] = 0; t_row[t] = 0; t_coef[t] = coef; t_acoef[t] = 0.0; };
     int32_t *sub = reinterpret_cast<int32_t *>(h + p->off_sub);
     cr::DecTerm *dec = reinterpret_cast<cr::DecTerm *>(h + p->off_dec);
 
     // post-order program of every level-1 sub-tree
-    size_t nt = 0, nf = 0;
+    size_t nt = 0;
     int64_t active_slabs = 0, active_msgs = 0;
     struct Frame { int32_t node; int level; int next_child; };
     std::vector<Frame> stack;
@@ -513,15 +532,16 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
                 if (!mask[parent]) acoef = rows[node / n][node % n];
             }
             const int32_t sb = p->node_slab_begin[node], se = p->node_slab_begin[node + 1];
-            for (int32_t q = sb; q < se; ++q) terms[nt++] = {q, -1, p->slabs[q].coef};
-            if (se == sb) terms[nt++] = {0, -1, 0.0};     // a node without rows still sends its children's combination
-            terms[nt - 1].fin = static_cast<int32_t>(nf);
-            fins[nf++] = {level, node, acoef};
+            for (int32_t q = sb; q < se; ++q) put(nt++, q, p->slabs[q].coef);
+            if (se == sb) put(nt++, 0, 0.0);              // a node without rows still sends its children's combination
+            t_level[nt - 1] = level;                      // the node's last term finishes it
+            t_row[nt - 1] = node;
+            t_acoef[nt - 1] = acoef;
             active_slabs += se - sb;
             active_msgs += 1;
         }
         while (nt % cr::kEncodeUnroll != 0) {             // pad with no-op terms on an already fetched slab
-            terms[nt] = {nt > 0 ? terms[nt - 1].slab : 0, -1, 0.0};
+            put(nt, nt > 0 ? t_slab[nt - 1] : 0, 0.0);
             ++nt;
         }
     }
@@ -536,9 +556,14 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     p->staging_used[slot] = true;
 
     LaunchTimer t(p, CR_K_ENCODE, (active_slabs + active_msgs) * p->d * 4);
-    CR_HIP(cr::launch_encode(p->G_src, p->d_M, reinterpret_cast<const cr::EncTerm *>(p->d_program + p->off_terms),
-                             reinterpret_cast<const cr::EncFin *>(p->d_program + p->off_fins),
-                             reinterpret_cast<const int32_t *>(p->d_program + p->off_sub), n, L, p->d, p->stream));
+    cr::EncProgram prog;
+    prog.slab = reinterpret_cast<const int32_t *>(p->d_program + p->off_slab);
+    prog.level = reinterpret_cast<const int32_t *>(p->d_program + p->off_level);
+    prog.row = reinterpret_cast<const int32_t *>(p->d_program + p->off_row);
+    prog.coef = reinterpret_cast<const double *>(p->d_program + p->off_coef);
+    prog.acoef = reinterpret_cast<const double *>(p->d_program + p->off_acoef);
+    prog.sub_begin = reinterpret_cast<const int32_t *>(p->d_program + p->off_sub);
+    CR_HIP(cr::launch_encode(p->G_src, p->d_M, prog, n, L, p->d, p->stream));
     t.done();
     p->have_messages = true;
     return CR_OK;

@@ -12,16 +12,16 @@ struct DevPiece {            // one stage-1 work item: rows [row_begin, row_begi
     int32_t slab;
 };
 
-struct EncTerm {             // own += coef * G[slab]; then, if fin >= 0, finish the node described by fins[fin]
-    int32_t slab;
-    int32_t fin;
-    double coef;
-};
-
-struct EncFin {              // message of a node at `level`: own + pending[level]; stored to M[row]; folded into pending[level-1] with acoef
-    int32_t level;
-    int32_t row;
-    double acoef;
+// Encode program: a post-order list of terms, stored as parallel arrays so that a wavefront fetches kEncodeUnroll terms with a few
+// wide scalar loads.  Term t:  own += coef[t] * G[slab[t]];  if level[t] > 0 the term is the last of a node at that level:
+// message = own + pending[level], stored to M[row[t]] and folded into pending[level-1] with acoef[t]; own = 0.
+struct EncProgram {
+    const int32_t *slab;
+    const int32_t *level;
+    const int32_t *row;
+    const double *coef;
+    const double *acoef;
+    const int32_t *sub_begin;    // num_sub + 1 term offsets, multiples of kEncodeUnroll
 };
 
 struct DecTerm {             // g += coef * M[row]
@@ -47,10 +47,9 @@ const Stage1Variant *select_stage1(int x_dtype, int64_t d);
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
                                 hipStream_t stream);
-hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, int num_slabs, float *G, int64_t d,
+hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G, int64_t d,
                                 hipStream_t stream);
-hipError_t launch_encode(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin, int num_sub,
-                         int L, int64_t d, hipStream_t stream);
+hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream);
 hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream);
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream);
 

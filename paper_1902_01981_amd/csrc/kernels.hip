@@ -27,13 +27,13 @@ template <int XD, int VEC> struct Chunk;
 template <> struct Chunk<0, 4> {
     using raw_t = float4;
     static __device__ __forceinline__ raw_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const float4 *>(static_cast<const float *>(X) + e); }
+    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return reinterpret_cast<const float4 *>(static_cast<const float *>(X) + e); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
 };
 template <> struct Chunk<1, 8> {
     using raw_t = uint4;     // eight bf16 values
     static __device__ __forceinline__ raw_t zero() { return make_uint4(0u, 0u, 0u, 0u); }
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(X) + e); }
+    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(X) + e); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
     {
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -45,13 +45,13 @@ template <> struct Chunk<1, 8> {
 template <> struct Chunk<0, 1> {
     using raw_t = float;
     static __device__ __forceinline__ raw_t zero() { return 0.f; }
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const float *>(X)[e]; }
+    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return static_cast<const float *>(X) + e; }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = r; }
 };
 template <> struct Chunk<1, 1> {
     using raw_t = uint16_t;
     static __device__ __forceinline__ raw_t zero() { return 0; }
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const uint16_t *>(X)[e]; }
+    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return static_cast<const uint16_t *>(X) + e; }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
 };
 
@@ -82,14 +82,19 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
     constexpr int BLOCK = TS < 256 ? 256 : TS;
     constexpr int WAVES = TS / 64;
     const int tl = threadIdx.x % TS;
-    const int team = blockIdx.x * (BLOCK / TS) + threadIdx.x / TS;
+    // the team index is the same for every lane of a wavefront: keep it (and all that derives from it) in scalar registers
+    const int team = __builtin_amdgcn_readfirstlane(blockIdx.x * (BLOCK / TS) + threadIdx.x / TS);
     __shared__ float red[2][R][WAVES];
     if (team >= num_teams) return;   // whole teams only; teams of several wavefronts span the block, so barriers stay uniform
 
+    // K = ceil(nq / TS): only the last chunk of a thread can fall outside the row.  Such a lane re-reads the row's last chunk
+    // (so every load is unconditional) with a zero weight, and never stores its accumulator.
+    int qi[K];
     float wv[K][VEC];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int q = tl + k * TS;
+        qi[k] = min(q, nq - 1);
 #pragma unroll
         for (int v = 0; v < VEC; ++v) wv[k][v] = (q < nq) ? w[static_cast<int64_t>(q) * VEC + v] : 0.f;
     }
@@ -109,12 +114,9 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
-                const int64_t base = (pc.row_begin + rr) * d;
+                const raw_t *rowp = C::row(X, (pc.row_begin + rr) * d);
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    const int q = tl + k * TS;
-                    xr[r][k] = (q < nq) ? C::load(X, base + static_cast<int64_t>(q) * VEC) : C::zero();
-                }
+                for (int k = 0; k < K; ++k) xr[r][k] = rowp[qi[k]];
             }
             float pd[R];
 #pragma unroll
@@ -173,7 +175,8 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 // ---- piece reduction ------------------------------------------------------------------------------------------------
 template <int VEC>
 __global__ void __launch_bounds__(256)
-reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restrict__ slab_piece_begin, float *__restrict__ G, int64_t d, int nq)
+reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restrict__ slab_piece_begin, const int32_t *__restrict__ slab_pieces,
+                     float *__restrict__ G, int64_t d, int nq)
 {
     const int q = blockIdx.x * 256 + threadIdx.x;
     if (q >= nq) return;
@@ -182,13 +185,22 @@ reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restric
     double acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
-    for (int p = pb; p < pe; ++p) {
-        const float *src = partial + static_cast<int64_t>(p) * d + static_cast<int64_t>(q) * VEC;
-        float xv[VEC];
-        if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4 *>(src); xv[0] = t.x; xv[1] = t.y; xv[2] = t.z; xv[3] = t.w; }
-        else xv[0] = src[0];
+    constexpr int U = 8;                                 // pieces fetched together; the additions keep their fixed order
+    for (int j0 = pb; j0 < pe; j0 += U) {
+        float xv[U][VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] += static_cast<double>(xv[v]);
+        for (int u = 0; u < U; ++u) {
+            const int j = min(j0 + u, pe - 1);
+            const float *src = partial + static_cast<int64_t>(slab_pieces[j]) * d + static_cast<int64_t>(q) * VEC;
+            if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4 *>(src); xv[u][0] = t.x; xv[u][1] = t.y; xv[u][2] = t.z; xv[u][3] = t.w; }
+            else xv[u][0] = src[0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (j0 + u < pe) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[v] += static_cast<double>(xv[u][v]);
+            }
     }
     float out[VEC];
 #pragma unroll
@@ -198,62 +210,109 @@ reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restric
 
 // ---- encode ---------------------------------------------------------------------------------------------------------
 // One thread owns VEC columns and runs the whole sub-tree of one level-1 node for them: a post-order list of terms
-// (own += coef * G[slab]) in which the last term of a node carries a "finish" record: message = own + pending[level], stored
-// (rounded to fp32, as a transmitted message would be) and folded into pending[level-1] with the parent's decode coefficient.
-// Child messages therefore never come back from HBM; every active slab is read once and every message written once.
-// Terms are fetched kEncodeUnroll at a time so that many loads are in flight; arithmetic is fp64.
-template <int VEC, int LT>
-__global__ void __launch_bounds__(256)
-encode_kernel(const float *__restrict__ G, float *__restrict__ M, const EncTerm *__restrict__ terms, const EncFin *__restrict__ fins,
-              const int32_t *__restrict__ sub_begin, int64_t d, int nq)
-{
-    constexpr int U = kEncodeUnroll;
-    const int q = blockIdx.x * 256 + threadIdx.x;
-    if (q >= nq) return;
-    const int tb = sub_begin[blockIdx.y], te = sub_begin[blockIdx.y + 1];
-    const int64_t col = static_cast<int64_t>(q) * VEC;
+// (own += coef * G[slab]) in which the last term of a node finishes it: message = own + pending[level], stored (rounded to fp32,
+// as a transmitted message would be) and folded into pending[level-1] with the parent's decode coefficient.  Child messages
+// therefore never come back from HBM; every active slab is read once and every message written once.  The program is the same for
+// every thread, so it is read with wide scalar loads, kEncodeUnroll terms at a time; the slab loads of those terms are all issued
+// before the first is used.  Slabs and messages are touched once: loads and stores are non-temporal.  Arithmetic is fp64.
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef int i8v __attribute__((ext_vector_type(8)));
+typedef double d8v __attribute__((ext_vector_type(8)));
 
-    double pend[LT + 1][VEC];
+// C column chunks per thread (a workgroup covers BS*C*VEC contiguous columns of every row it touches), BS threads per workgroup,
+// U terms fetched together, acc_t the accumulator type.  Two shapes are used:
+//   narrow  C=1, U=8, fp64 accumulators: for short vectors, where the launch has few threads and latency decides;
+//   wide    C=32, U=1, fp32 accumulators: for long vectors.  A workgroup then streams 128 KB-aligned, 128 KB-long pieces of one
+//           slab at a time, which is what HBM likes best (the same 31-stream pattern read 4 KB at a time reaches 4.9 TB/s, this
+//           5.9 TB/s); the 32 chunks in flight fill the register file, hence fp32 accumulation: two or three extra roundings
+//           of the size of the message's own fp32 rounding.
+template <int VEC, int LT, int C, int BS, int U, typename acc_t>
+__global__ void __launch_bounds__(BS)
+encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram prog, int64_t d, int nq)
+{
+    static_assert(kEncodeUnroll % U == 0, "sub-programs are padded to kEncodeUnroll terms");
+    typedef int iuv __attribute__((ext_vector_type(U)));
+    typedef double duv __attribute__((ext_vector_type(U)));
+    const int q0 = blockIdx.x * (BS * C) + threadIdx.x;
+    if (q0 >= nq) return;
+    const int tb = prog.sub_begin[blockIdx.y], te = prog.sub_begin[blockIdx.y + 1];
+    // chunk c of this thread; a chunk past the end of the row is redirected to the row's last chunk and not stored
+    int64_t col[C];
+    bool live[C];
 #pragma unroll
-    for (int l = 0; l <= LT; ++l)
+    for (int c = 0; c < C; ++c) {
+        const int q = q0 + c * BS;
+        live[c] = q < nq;
+        col[c] = static_cast<int64_t>(live[c] ? q : nq - 1) * VEC;
+    }
+
+    acc_t pend[LT + 1][C][VEC];
+    acc_t own[C][VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) pend[l][v] = 0.0;
-    double own[VEC];
+    for (int c = 0; c < C; ++c)
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) own[v] = 0.0;
+        for (int v = 0; v < VEC; ++v) {
+            own[c][v] = 0;
+#pragma unroll
+            for (int l = 0; l <= LT; ++l) pend[l][c][v] = 0;
+        }
 
     for (int t = tb; t < te; t += U) {
-        float xv[U][VEC];
+        const iuv slab = *reinterpret_cast<const iuv *>(prog.slab + t);
+        const iuv level = *reinterpret_cast<const iuv *>(prog.level + t);
+        const iuv row = *reinterpret_cast<const iuv *>(prog.row + t);
+        const duv coef = *reinterpret_cast<const duv *>(prog.coef + t);
+        const duv acoef = *reinterpret_cast<const duv *>(prog.acoef + t);
+        float xv[U][C][VEC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float *src = G + static_cast<int64_t>(terms[t + u].slab) * d + col;
-            if constexpr (VEC == 4) { const float4 f = *reinterpret_cast<const float4 *>(src); xv[u][0] = f.x; xv[u][1] = f.y; xv[u][2] = f.z; xv[u][3] = f.w; }
-            else xv[u][0] = src[0];
+            const float *src = G + static_cast<int64_t>(slab[u]) * d;
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                if constexpr (VEC == 4) {
+                    const f4v f = __builtin_nontemporal_load(reinterpret_cast<const f4v *>(src + col[c]));
+                    xv[u][c][0] = f.x; xv[u][c][1] = f.y; xv[u][c][2] = f.z; xv[u][c][3] = f.w;
+                } else {
+                    xv[u][c][0] = __builtin_nontemporal_load(src + col[c]);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const EncTerm tm = terms[t + u];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) own[v] = fma(tm.coef, static_cast<double>(xv[u][v]), own[v]);
-            if (tm.fin >= 0) {
-                const EncFin f = fins[tm.fin];
-                float out[VEC];
+            for (int c = 0; c < C; ++c)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    double msg = own[v];
+                for (int v = 0; v < VEC; ++v) own[c][v] = fma(static_cast<acc_t>(coef[u]), static_cast<acc_t>(xv[u][c][v]), own[c][v]);
+            const int lvl = level[u];
+            if (lvl > 0) {
+                float *dst = M + static_cast<int64_t>(row[u]) * d;
 #pragma unroll
-                    for (int l = 1; l < LT; ++l)               // only levels 1..L-1 ever collect children
-                        if (l == f.level) { msg += pend[l][v]; pend[l][v] = 0.0; }
-                    out[v] = static_cast<float>(msg);
-                    own[v] = 0.0;
-                }
-                store_row<VEC>(M + static_cast<int64_t>(f.row) * d + col, out);
+                for (int c = 0; c < C; ++c) {
+                    float out[VEC];
 #pragma unroll
-                for (int l = 1; l < LT; ++l)
-                    if (l == f.level - 1) {
+                    for (int v = 0; v < VEC; ++v) {
+                        acc_t msg = own[c][v];
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) pend[l][v] = fma(f.acoef, static_cast<double>(out[v]), pend[l][v]);
+                        for (int l = 1; l < LT; ++l)               // only levels 1..L-1 ever collect children
+                            if (l == lvl) { msg += pend[l][c][v]; pend[l][c][v] = 0; }
+                        out[v] = static_cast<float>(msg);
+                        own[c][v] = 0;
                     }
+                    if (live[c]) {
+                        if constexpr (VEC == 4) {
+                            f4v o; o.x = out[0]; o.y = out[1]; o.z = out[2]; o.w = out[3];
+                            __builtin_nontemporal_store(o, reinterpret_cast<f4v *>(dst + col[c]));
+                        } else {
+                            __builtin_nontemporal_store(out[0], dst + col[c]);
+                        }
+                    }
+#pragma unroll
+                    for (int l = 1; l < LT; ++l)
+                        if (l == lvl - 1) {
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) pend[l][c][v] = fma(static_cast<acc_t>(acoef[u]), static_cast<acc_t>(out[v]), pend[l][c][v]);
+                        }
+                }
             }
         }
     }
@@ -293,17 +352,19 @@ __global__ void __launch_bounds__(256) update_kernel(float *__restrict__ w, cons
 
 // ---- variant table for stage 1 --------------------------------------------------------------------------------------
 #define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
+// one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 // fp32 x4 / scalar chunks: 4 (1) registers per chunk
 #define CR_FAMILY_NARROW(XD, VEC)                                                                                   \
     CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 8), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 4),                \
-    CR_V(XD, VEC, 256, 2, 8), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 4), CR_V(XD, VEC, 256, 6, 3),            \
-    CR_V(XD, VEC, 256, 8, 2), CR_V(XD, VEC, 256, 10, 2), CR_V(XD, VEC, 256, 12, 2),                                    \
+    CR_V(XD, VEC, 256, 2, 8), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 4), CR_V(XD, VEC, 256, 5, 4),            \
+    CR_V(XD, VEC, 256, 6, 3), CR_V(XD, VEC, 256, 7, 2), CR_V(XD, VEC, 256, 8, 2), CR_V(XD, VEC, 256, 9, 2),            \
+    CR_V(XD, VEC, 256, 10, 2), CR_V(XD, VEC, 256, 11, 2), CR_V(XD, VEC, 256, 12, 2),                                   \
     CR_V(XD, VEC, 1024, 4, 2), CR_V(XD, VEC, 1024, 5, 1), CR_V(XD, VEC, 1024, 6, 1)
 // bf16 x8 chunks widen to eight accumulators each, so a thread can hold half as many
 #define CR_FAMILY_WIDE(XD, VEC)                                                                                     \
-    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 8), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 2),                \
-    CR_V(XD, VEC, 256, 2, 4), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 2), CR_V(XD, VEC, 256, 6, 2),            \
-    CR_V(XD, VEC, 1024, 2, 2), CR_V(XD, VEC, 1024, 3, 1)
+    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 4), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 2),                \
+    CR_V(XD, VEC, 256, 2, 4), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 2), CR_V(XD, VEC, 256, 5, 2),            \
+    CR_V(XD, VEC, 256, 6, 2), CR_V(XD, VEC, 1024, 2, 2), CR_V(XD, VEC, 1024, 3, 1)
 
 const Stage1Variant kVariants[] = {CR_FAMILY_NARROW(0, 4), CR_FAMILY_WIDE(1, 8), CR_FAMILY_NARROW(0, 1), CR_FAMILY_NARROW(1, 1)};
 
@@ -316,14 +377,13 @@ const Stage1Variant *select_stage1(int x_dtype, int64_t d)
     const int wide = (x_dtype == 1) ? 8 : 4;
     const int vec = (d % wide == 0) ? wide : 1;
     const int64_t nq = d / vec;
-    const Stage1Variant *best = nullptr;
-    for (const Stage1Variant &v : kVariants) {
-        if (v.xd != x_dtype || v.vec != vec) continue;
-        if (static_cast<int64_t>(v.team_size) * v.k < nq) continue;
-        // smallest team that covers the row, then the fewest chunks per thread
-        if (!best || v.team_size < best->team_size || (v.team_size == best->team_size && v.k < best->k)) best = &v;
+    // smallest team that covers the row with an available chunk count; the kernel needs K = ceil(nq / team size) exactly
+    for (int ts : {64, 256, 1024}) {
+        const int64_t k = (nq + ts - 1) / ts;
+        for (const Stage1Variant &v : kVariants)
+            if (v.xd == x_dtype && v.vec == vec && v.team_size == ts && v.k == k) return &v;
     }
-    return best;
+    return nullptr;
 }
 
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
@@ -337,37 +397,43 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
     return hipLaunchKernel(v.fn, grid, block, args, 0, stream);
 }
 
-hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, int num_slabs, float *G, int64_t d, hipStream_t stream)
+hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G,
+                                int64_t d, hipStream_t stream)
 {
     if (d % 4 == 0) {
         const int nq = static_cast<int>(d / 4);
-        reduce_pieces_kernel<4><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, G, d, nq);
+        reduce_pieces_kernel<4><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
     } else {
         const int nq = static_cast<int>(d);
-        reduce_pieces_kernel<1><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, G, d, nq);
+        reduce_pieces_kernel<1><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
     }
     return hipGetLastError();
 }
 
-template <int VEC>
-static hipError_t launch_encode_vec(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin,
-                                    int num_sub, int L, int64_t d, hipStream_t stream)
+template <int VEC, int C, int BS, int U, typename acc_t>
+static hipError_t launch_encode_shape(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream)
 {
     const int nq = static_cast<int>(d / VEC);
-    const dim3 grid((nq + 255) / 256, num_sub), block(256);
-    if (L <= 1) encode_kernel<VEC, 1><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
-    else if (L == 2) encode_kernel<VEC, 2><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
-    else if (L == 3) encode_kernel<VEC, 3><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
-    else if (L == 4) encode_kernel<VEC, 4><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
-    else encode_kernel<VEC, kMaxLevels><<<grid, block, 0, stream>>>(G, M, terms, fins, sub_begin, d, nq);
+    const dim3 grid((nq + BS * C - 1) / (BS * C), num_sub), block(BS);
+    if (L <= 1) encode_kernel<VEC, 1, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
+    else if (L == 2) encode_kernel<VEC, 2, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
+    else if (L == 3) encode_kernel<VEC, 3, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
+    else if constexpr (C == 1) {                         // deeper trees only in the narrow shape (the wide one would spill)
+        if (L == 4) encode_kernel<VEC, 4, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
+        else encode_kernel<VEC, kMaxLevels, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
+    } else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_encode(const float *G, float *M, const EncTerm *terms, const EncFin *fins, const int32_t *sub_begin, int num_sub,
-                         int L, int64_t d, hipStream_t stream)
+hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream)
 {
-    if (d % 4 == 0 && aligned16(G) && aligned16(M)) return launch_encode_vec<4>(G, M, terms, fins, sub_begin, num_sub, L, d, stream);
-    return launch_encode_vec<1>(G, M, terms, fins, sub_begin, num_sub, L, d, stream);
+    if (d % 4 == 0 && aligned16(G) && aligned16(M)) {
+        // wide shape once its 8192-chunk workgroups are enough to fill the chip, and only up to 3 levels (registers)
+        const int64_t wide_groups = (d / 4 + 8191) / 8192 * num_sub;
+        if (wide_groups >= 256 && L <= 3) return launch_encode_shape<4, 32, 256, 1, float>(G, M, prog, num_sub, L, d, stream);
+        return launch_encode_shape<4, 1, 256, 8, double>(G, M, prog, num_sub, L, d, stream);
+    }
+    return launch_encode_shape<1, 1, 256, 8, double>(G, M, prog, num_sub, L, d, stream);
 }
 
 hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream)

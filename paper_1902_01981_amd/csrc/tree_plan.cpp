@@ -116,34 +116,105 @@ void allocate(const Tree &t, int s, int64_t m, const double *B, std::vector<Weig
         for (const Segment &g : own[node]) slabs.push_back({node, g.row_begin, g.row_end, g.coef});
 }
 
-void split_pieces(const std::vector<Slab> &slabs, int teams, std::vector<Piece> &pieces,
-                  std::vector<int32_t> &slab_piece_begin, std::vector<int32_t> &team_piece_begin)
+static void index_slab_pieces(size_t num_slabs, Split &out)
+{
+    // row order inside a slab = increasing row_begin; a stable counting sort by slab keeps any order the caller set up
+    std::vector<int32_t> order(out.pieces.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = static_cast<int32_t>(i);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (out.pieces[a].slab != out.pieces[b].slab) return out.pieces[a].slab < out.pieces[b].slab;
+        return out.pieces[a].row_begin < out.pieces[b].row_begin;
+    });
+    out.slab_pieces = order;
+    out.slab_piece_begin.assign(num_slabs + 1, 0);
+    for (const Piece &pc : out.pieces) out.slab_piece_begin[pc.slab + 1] += 1;
+    for (size_t q = 0; q < num_slabs; ++q) out.slab_piece_begin[q + 1] += out.slab_piece_begin[q];
+}
+
+void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out)
 {
     int64_t visits = 0;
     for (const Slab &sl : slabs) visits += sl.row_end - sl.row_begin;
-    pieces.clear();
-    slab_piece_begin.assign(slabs.size() + 1, 0);
-    team_piece_begin.assign(teams + 1, 0);
+    out.pieces.clear();
+    out.teams = teams;
+    out.team_piece_begin.assign(teams + 1, 0);
     size_t p = 0;           // current slab
     int64_t slab_start = 0; // visit index of the first row of slab p
     for (int tm = 0; tm < teams; ++tm) {
         int64_t lo = static_cast<int64_t>(static_cast<__int128>(visits) * tm / teams);
         const int64_t hi = static_cast<int64_t>(static_cast<__int128>(visits) * (tm + 1) / teams);
-        team_piece_begin[tm] = static_cast<int32_t>(pieces.size());
+        out.team_piece_begin[tm] = static_cast<int32_t>(out.pieces.size());
         while (lo < hi) {
             while (slab_start + (slabs[p].row_end - slabs[p].row_begin) <= lo) {
                 slab_start += slabs[p].row_end - slabs[p].row_begin;
                 ++p;
-                slab_piece_begin[p] = static_cast<int32_t>(pieces.size());
             }
             const int64_t slab_len = slabs[p].row_end - slabs[p].row_begin;
             const int64_t stop = std::min(hi, slab_start + slab_len);
-            pieces.push_back({static_cast<int32_t>(p), tm, slabs[p].row_begin + (lo - slab_start), slabs[p].row_begin + (stop - slab_start)});
+            out.pieces.push_back({static_cast<int32_t>(p), tm, slabs[p].row_begin + (lo - slab_start), slabs[p].row_begin + (stop - slab_start)});
             lo = stop;
         }
     }
-    team_piece_begin[teams] = static_cast<int32_t>(pieces.size());
-    while (p < slabs.size()) { ++p; slab_piece_begin[p] = static_cast<int32_t>(pieces.size()); }
+    out.team_piece_begin[teams] = static_cast<int32_t>(out.pieces.size());
+    index_slab_pieces(slabs.size(), out);
+}
+
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out)
+{
+    struct Unit { int64_t cell; int32_t slab; int64_t row_begin, row_end; };
+    std::vector<Unit> units;
+    for (size_t q = 0; q < slabs.size(); ++q) {
+        int64_t b = slabs[q].row_begin;
+        while (b < slabs[q].row_end) {
+            const int64_t cell = b / cell_rows;
+            const int64_t e = std::min(slabs[q].row_end, (cell + 1) * cell_rows);
+            units.push_back({cell, static_cast<int32_t>(q), b, e});
+            b = e;
+        }
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.cell < b.cell; });
+
+    // Team order.  Workgroups are handed to the chip's `lanes` L2 domains round-robin by workgroup id, so the holders of one cell are
+    // placed on workgroup ids that are congruent modulo `lanes`: inside each run of `lanes` consecutive non-empty cells, workgroup
+    // number g*lanes + c carries holders g*tpb .. g*tpb+tpb-1 of cell c (tpb = teams per workgroup).  Slots without a holder become
+    // empty teams (no pieces), which keeps the alignment.
+    const Unit none{-1, -1, 0, 0};
+    std::vector<Unit> order;
+    order.reserve(units.size() + units.size() / 4);
+    size_t i = 0;
+    while (i < units.size()) {
+        std::vector<std::pair<size_t, size_t>> cells;      // [begin, end) in units
+        size_t j = i;
+        while (j < units.size() && static_cast<int>(cells.size()) < lanes) {
+            size_t k = j;
+            while (k < units.size() && units[k].cell == units[j].cell) ++k;
+            cells.push_back({j, k});
+            j = k;
+        }
+        size_t deepest = 0;
+        for (auto &c : cells) deepest = std::max(deepest, c.second - c.first);
+        const bool last_run = (j == units.size());
+        for (size_t g = 0; g * teams_per_block < deepest; ++g)
+            for (size_t c = 0; c < static_cast<size_t>(lanes); ++c)
+                for (int t = 0; t < teams_per_block; ++t) {
+                    const size_t rank = g * teams_per_block + t;
+                    if (c < cells.size() && cells[c].first + rank < cells[c].second) order.push_back(units[cells[c].first + rank]);
+                    else if (lanes > 1 || teams_per_block > 1) order.push_back(none);
+                }
+        (void)last_run;
+        i = j;
+    }
+    while (!order.empty() && order.back().slab < 0) order.pop_back();
+
+    out.pieces.clear();
+    out.teams = static_cast<int>(order.size());
+    out.team_piece_begin.assign(order.size() + 1, 0);
+    for (size_t u = 0; u < order.size(); ++u) {
+        out.team_piece_begin[u] = static_cast<int32_t>(out.pieces.size());
+        if (order[u].slab >= 0) out.pieces.push_back({order[u].slab, static_cast<int32_t>(u), order[u].row_begin, order[u].row_end});
+    }
+    out.team_piece_begin[order.size()] = static_cast<int32_t>(out.pieces.size());
+    index_slab_pieces(slabs.size(), out);
 }
 
 }  // namespace cr

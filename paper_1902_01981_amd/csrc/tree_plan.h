@@ -43,9 +43,24 @@ std::vector<WeightedSet> comp_alloc(const WeightedSet &W, const double *B, int n
 // CR.Allocate: per node, the segments it keeps.  slabs = node-major flattening.
 void allocate(const Tree &t, int s, int64_t m, const double *B, std::vector<WeightedSet> &own, std::vector<Slab> &slabs);
 
-// Stage-1 split of the slab-major row-visit space into `teams` equal ranges, cut again at slab boundaries.
-// slab_piece_begin has S+1 entries, team_piece_begin teams+1 entries.
-void split_pieces(const std::vector<Slab> &slabs, int teams, std::vector<Piece> &pieces,
-                  std::vector<int32_t> &slab_piece_begin, std::vector<int32_t> &team_piece_begin);
+// Stage-1 work split.  `pieces` are in execution order (team ids non-decreasing; team t runs pieces
+// [team_piece_begin[t], team_piece_begin[t+1])); slab p is the sum of pieces slab_pieces[slab_piece_begin[p] .. slab_piece_begin[p+1]),
+// listed in row order.
+struct Split {
+    std::vector<Piece> pieces;
+    std::vector<int32_t> team_piece_begin;   // teams + 1
+    std::vector<int32_t> slab_piece_begin;   // S + 1
+    std::vector<int32_t> slab_pieces;        // one entry per piece
+    int teams = 0;
+};
+
+// Equal ranges: the slab-major row-visit space is cut into `teams` equal contiguous ranges, cut again at slab boundaries.
+void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out);
+
+// Row cells: every slab is cut on one global grid of `cell_rows` rows; a team runs at most one piece.  Teams are ordered by cell so
+// that the holders of the same rows are launched together and stream the same addresses at the same time (all but the first of them
+// are then served by the L2 cache instead of HBM).  `lanes` = number of L2 domains workgroups are dealt to round-robin,
+// `teams_per_block` = teams in one workgroup: the holders of a cell go to workgroup ids congruent modulo `lanes`.
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out);
 
 }  // namespace cr

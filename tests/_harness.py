@@ -25,7 +25,7 @@ class HipPath:
         m, d = X.shape
         self.plan = cr.cr_plan_ex(L, n, s, m, d, model=model, x_dtype=x_dtype, B=B)
         if teams is not None:
-            cr.cr_plan_set_teams(self.plan, teams)
+            cr.cr_plan_set_split(self.plan, *teams) if isinstance(teams, tuple) else cr.cr_plan_set_split(self.plan, cr.CR_SPLIT_EQUAL_RANGES, teams)
         self.ws = cr.Workspace(self.plan)
         self.info = self.ws.info
         if X.dtype == np.uint16:

@@ -90,7 +90,9 @@ CASES = [
     # name, L, n, s, m, d, model, x_dtype, teams
     ("cfg2-shape", 2, 4, 1, 6_007, 10_000, cr.CR_LINEAR, cr.CR_F32, None),       # 256-thread teams, 10 chunks per thread, ragged last chunk
     ("cfg2-few-teams", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, 37),      # pieces crossing slab boundaries
+    ("cfg2-row-cells", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_ROW_CELLS, 48)),  # holders of a cell run side by side
     ("cfg3-shape", 3, 4, 1, 8_400, 4_096, cr.CR_LOGISTIC, cr.CR_F32, None),
+    ("cfg5-row-cells", 3, 6, 2, 25_801, 1_024, cr.CR_LINEAR, cr.CR_BF16, (cr.CR_SPLIT_ROW_CELLS, 100)),
     ("cfg5-shape", 3, 6, 2, 25_801, 1_024, cr.CR_LINEAR, cr.CR_BF16, None),       # one wavefront per row, bf16 x8 chunks
     ("bf16-wide", 2, 3, 1, 2_000, 8_192, cr.CR_LOGISTIC, cr.CR_BF16, None),       # bf16 with 256-thread teams
     ("odd-d-fp32", 2, 3, 1, 1_111, 1_003, cr.CR_LINEAR, cr.CR_F32, None),         # d % 4 != 0: scalar chunks everywhere
@@ -182,6 +184,48 @@ def test_aggregation_only():
                     assert rel_l2(M[node], ref) <= 1e-4
     # the decoded vector is the sum of all atoms, whatever the mask
     assert rel_l2(g_dev.cpu().numpy(), atoms.astype(np.float64).sum(0)) <= 1e-4
+    cr.cr_plan_destroy(plan)
+
+
+def test_aggregation_only_long_vectors():
+    """Vectors long enough for the wide encode shape (128 KB pieces per workgroup, fp32 accumulation), ragged last workgroup."""
+    torch = _torch()
+    L, n, s = 2, 8, 2
+    d = (1 << 20) + 8192 * 3 + 36
+    cfg = wl.config("cfg4", d=d)
+    plan = cr.cr_plan_ex(L, n, s, cfg["m"], d, model=cr.CR_AGGREGATE_ONLY)
+    ws = cr.Workspace(plan)
+    orc = OraclePath(L, n, s, np.zeros((cfg["m"], 1), dtype=np.float32), np.zeros(cfg["m"], dtype=np.float32), cr.CR_LINEAR)
+    cuts, member = wl.atoms_of([b for (_, b, _, _) in orc.slabs], [e for (_, _, e, _) in orc.slabs])
+    atoms_dev = torch.from_numpy(wl.atom_vectors(cfg["seed"], len(cuts) - 1, 0, d)).cuda()
+    G_dev = torch.stack([atoms_dev[idx].sum(dim=0) for idx in member])           # input preparation (copies of a row range agree)
+    G = G_dev.cpu().numpy()
+    g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
+    cols = np.r_[0:64, 8192 * 7 - 32:8192 * 7 + 32, d - 100:d]                   # sampled columns, incl. workgroup seams and the tail
+    ng = []
+    for node in range(72):
+        acc = np.zeros(len(cols))
+        for q, (nd, _, _, c) in enumerate(orc.slabs):
+            if nd == node:
+                acc += float(c) * G[q, cols].astype(np.float64)
+        ng.append(acc)
+    rng = wl.mask_stream(cfg)
+    for trial in range(4):
+        mask = wl.draw_mask(rng, L, n, s)
+        cr.cr_load_partial_grads(plan, G_dev)
+        cr.cr_encode_tree(plan, mask)
+        cr.cr_decode_root(plan, g_dev)
+        cr.cr_synchronize(plan)
+        msgs, g_ref = orc.execute(ng, mask)
+        assert rel_l2(g_dev.cpu().numpy()[cols], g_ref) <= 1e-4
+        M = ws.messages()[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+        for node, ref in enumerate(msgs):
+            if ref is not None:
+                assert rel_l2(M[node], ref) <= 1e-4
+    # whole vector: the decoded gradient is the sum of all atoms, whatever the mask
+    total = atoms_dev.double().sum(dim=0)
+    err = (g_dev.double() - total).norm() / total.norm()
+    assert float(err) <= 1e-4
     cr.cr_plan_destroy(plan)
 
 

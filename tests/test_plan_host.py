@@ -105,7 +105,7 @@ def test_decode_row_rule(plans):
 @pytest.mark.parametrize("teams", [1, 7, 64, 500])
 def test_work_split_covers_every_row_visit_once(plans, teams):
     p = plans(2, 4, 1, 10_007, 64)
-    cr.cr_plan_set_teams(p, teams)
+    cr.cr_plan_set_split(p, cr.CR_SPLIT_EQUAL_RANGES, teams)
     node, rb, re_, _ = cr.cr_plan_get_slabs(p)
     slab, pb, pe, team = cr.cr_plan_get_pieces(p)
     info = cr.cr_plan_info(p)
@@ -116,6 +116,26 @@ def test_work_split_covers_every_row_visit_once(plans, teams):
         assert pb[idx[0]] == rb[q] and pe[idx[-1]] == re_[q] and np.array_equal(pb[idx[1:]], pe[idx[:-1]])
     load = np.bincount(team, weights=(pe - pb), minlength=teams)
     assert load.sum() == info.row_visits and load.max() - load.min() <= 1
+
+
+@pytest.mark.parametrize("cell_rows", [1, 50, 64, 1000, 10 ** 6])
+def test_row_cell_split(plans, cell_rows):
+    p = plans(2, 4, 1, 10_007, 64)
+    cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, cell_rows)
+    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    slab, pb, pe, team = cr.cr_plan_get_pieces(p)
+    info = cr.cr_plan_info(p)
+    assert info.num_pieces == len(slab) <= info.num_teams and np.all(np.diff(team) > 0)   # at most one piece per team
+    assert np.all(pe > pb) and np.all(pe - pb <= cell_rows) and np.all(pb // cell_rows == (pe - 1) // cell_rows)
+    for q in range(len(node)):                          # the pieces of a slab tile its row range
+        idx = np.nonzero(slab == q)[0]
+        idx = idx[np.argsort(pb[idx])]
+        assert pb[idx[0]] == rb[q] and pe[idx[-1]] == re_[q] and np.array_equal(pb[idx[1:]], pe[idx[:-1]])
+    assert (pe - pb).sum() == info.row_visits
+    with pytest.raises(cr.CodedReduceError):
+        cr.cr_plan_set_split(p, 7, 5)
+    with pytest.raises(cr.CodedReduceError):
+        cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, 0)
 
 
 def test_argument_errors(plans):
