@@ -160,7 +160,7 @@ void compute_layout(cr_plan_t *p, size_t *total)
     p->off_row = off;   off = align_up(off + p->max_terms * sizeof(int32_t), 256);
     p->off_coef = off;  off = align_up(off + p->max_terms * sizeof(double), 256);
     p->off_acoef = off; off = align_up(off + p->max_terms * sizeof(double), 256);
-    p->off_sub = off;   off = align_up(off + (p->n + 1) * sizeof(int32_t), 256);
+    p->off_sub = off;   off = align_up(off + 2 * static_cast<size_t>(p->n) * sizeof(int32_t), 256);   // begin and end of every sub-program
     p->off_dec = off;   off = align_up(off + p->n * sizeof(cr::DecTerm), 256);
     p->program_bytes = off;
 
@@ -514,6 +514,7 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     std::vector<Frame> stack;
     for (int i = 0; i < n; ++i) {
         sub[i] = static_cast<int32_t>(nt);
+        size_t real_terms = 0;
         stack.push_back({static_cast<int32_t>(i), 1, 0});
         while (!stack.empty()) {
             Frame &f = stack.back();
@@ -541,12 +542,13 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
             active_slabs += se - sb;
             active_msgs += 1;
         }
+        real_terms = nt - static_cast<size_t>(sub[i]);
         while (nt % cr::kEncodeUnroll != 0) {             // pad with no-op terms on an already fetched slab
             put(nt, nt > 0 ? t_slab[nt - 1] : 0, 0.0);
             ++nt;
         }
+        sub[n + i] = sub[i] + static_cast<int32_t>(real_terms);
     }
-    sub[n] = static_cast<int32_t>(nt);
     int ndec = 0;
     for (int j = 0; j < n; ++j)
         if (!mask[j] && rows[0][j] != 0.0) dec[ndec++] = {j, 0, rows[0][j]};
@@ -564,6 +566,7 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     prog.coef = reinterpret_cast<const double *>(p->d_program + p->off_coef);
     prog.acoef = reinterpret_cast<const double *>(p->d_program + p->off_acoef);
     prog.sub_begin = reinterpret_cast<const int32_t *>(p->d_program + p->off_sub);
+    prog.sub_end = prog.sub_begin + n;
     CR_HIP(cr::launch_encode(p->G_src, p->d_M, prog, n, L, p->d, p->stream));
     t.done();
     p->have_messages = true;

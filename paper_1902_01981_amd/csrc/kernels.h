@@ -21,7 +21,8 @@ struct EncProgram {
     const int32_t *row;
     const double *coef;
     const double *acoef;
-    const int32_t *sub_begin;    // num_sub + 1 term offsets, multiples of kEncodeUnroll
+    const int32_t *sub_begin;    // first term of each sub-program, a multiple of kEncodeUnroll
+    const int32_t *sub_end;      // one past its last real term; no-op terms pad it up to the next multiple of kEncodeUnroll
 };
 
 struct DecTerm {             // g += coef * M[row]

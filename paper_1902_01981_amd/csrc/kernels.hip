@@ -235,7 +235,8 @@ encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram pro
     typedef double duv __attribute__((ext_vector_type(U)));
     const int q0 = blockIdx.x * (BS * C) + threadIdx.x;
     if (q0 >= nq) return;
-    const int tb = prog.sub_begin[blockIdx.y], te = prog.sub_begin[blockIdx.y + 1];
+    // whole groups of U terms: the padding terms are only fetched when U does not divide the real length
+    const int tb = prog.sub_begin[blockIdx.y], te = tb + (prog.sub_end[blockIdx.y] - tb + U - 1) / U * U;
     // chunk c of this thread; a chunk past the end of the row is redirected to the row's last chunk and not stored
     int64_t col[C];
     bool live[C];
