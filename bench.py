@@ -29,6 +29,7 @@ DESCRIPTIONS = {
     "cfg3": "CR tree L=3 n=4 s=1 (84 workers), logistic regression fp32, m=252000 d=4096, random mask per step",
     "cfg4": "aggregation only: CR tree L=2 n=8 s=2 (72 workers), 248 fp32 partition-gradient vectors of length 2^24, encode+decode",
     "cfg5": "CR tree L=3 n=6 s=2 (258 workers), linear regression, X bf16 / fp32 accumulate, m=2064000 d=1024, random mask per step",
+    "nn12": "aggregation only: CR tree L=2 n=12 s=3 (156 workers), fp32 partition-gradient vectors of length 117706 (network sized), encode+decode",
 }
 
 
@@ -52,7 +53,7 @@ def cpu_baseline(cfg, data, plan_B, w_host, mask, g_gpu, budget_s: float):
     from oracle import cr_tree, gc_code, native
 
     L, n, s = cfg["L"], cfg["n"], cfg["s"]
-    B = gc_code.search_encoding_matrix(n, s, 190201981)[0]
+    B = gc_code.design_code(n, s, L, 190201981)[0]
     own, _ = cr_tree.cr_allocate(L, n, s, cfg["m"], B)
     slabs = cr_tree.slabs_of(own)
     visits = sum(e - b for _, b, e, _ in slabs)

@@ -27,6 +27,9 @@ CONFIGS = {
     "cfg2": dict(L=2, n=4, s=1, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
     "cfg3": dict(L=3, n=4, s=1, m=252_000, d=4_096, model=LOGISTIC, x_dtype=F32, noise=0.1, steps=20, lr=1e-5, w0_std=None),
     "cfg4": dict(L=2, n=8, s=2, m=88, d=1 << 24, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
+    # the paper's simulated network training: (12,2) tree, 156 workers, about 120 000 parameters (5 layers: 3x16x3x3, 16x64x4x4,
+    # 64x384, 384x192, 192x10 weights plus biases = 117 706), aggregation only
+    "nn12": dict(L=2, n=12, s=3, m=156 * 40, d=117_706, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
     "cfg5": dict(L=3, n=6, s=2, m=2_064_000, d=1_024, model=LINEAR, x_dtype=BF16, noise=0.01, steps=100, lr=4e-7, w0_std=1.0),
 }
 
@@ -34,7 +37,7 @@ CONFIGS = {
 def config(name: str, **overrides) -> dict:
     cfg = dict(CONFIGS[name])
     cfg["name"] = name
-    cfg["seed"] = BASE_SEED + int(name[3:])
+    cfg["seed"] = BASE_SEED + (int(name[3:]) if name.startswith("cfg") else 12)
     cfg.update(overrides)
     return cfg
 

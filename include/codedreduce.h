@@ -65,7 +65,7 @@ typedef struct cr_plan_info {
     int32_t num_groups;      /* N / n sibling groups */
     int32_t num_slabs;       /* S: (worker, segment) pairs; one d-float partial gradient each */
     int32_t num_decode_rows; /* F = C(n,s) */
-    int32_t code_candidate;  /* index of the winning candidate of the code search, -1 if B was supplied */
+    int32_t code_candidate;  /* index of the winning candidate of the code search; -1 if B was supplied; -2 fractional repetition */
     int32_t num_teams;       /* stage-1 work split (0 until known, see cr_plan_set_split) */
     int32_t num_pieces;      /* stage-1 partial rows (0 until the split is known) */
     int64_t m, d;
@@ -77,12 +77,13 @@ typedef struct cr_plan_info {
 
 /* ---- plan (host only; Section III-A CR.Allocate, Algorithms 1 and 2, Section II-C for the code) ------------
  * cr_plan builds, on the host: the gradient-coding matrices B (n x n, cyclic support {i..i+s} mod n, unit-norm
- * rows) and the decode rows a_f (a_f B = 1, zero on the straggler set); the recursive allocation of weighted row
+ * rows; if the best cyclic candidate has gamma^L > 256 and s+1 divides n, the 0/1 fractional-repetition design
+ * instead) and the decode rows a_f (a_f B = 1, zero on the straggler set); the recursive allocation of weighted row
  * segments to every node (CompAlloc with k = n parts cut at floor(kappa |W| / n); a node keeps the first
  * round(|W| / sum_{j=0}^{L-l} (n/(s+1))^j) positions of its sub-tree set, leaves keep all); and the slab list
  * (node-major, segments in allocation order).  cr_plan = cr_plan_ex with CR_LINEAR, CR_F32, the default seed, no B.
  *   seed         seeds the counter-based search for a well-conditioned code (ignored when B is given)
- *   B_or_null    host, n*n doubles row-major: use this encoding matrix (support must be the cyclic window); or NULL
+ *   B_or_null    host, n*n doubles row-major: use this encoding matrix (s+1 non-zeros in every row and column); or NULL
  *   out          receives the plan; destroy with cr_plan_destroy
  * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, m<N, C(n,s) > 2^20, N > 2^24, a singular/unsupported B. */
 int cr_plan(int L, int n, int s, int64_t m, int64_t d, cr_plan_t **out);

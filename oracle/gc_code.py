@@ -23,6 +23,9 @@ The paper is silent on conditioning.  `search_encoding_matrix` draws K
 candidates for H from a counter-based generator (splitmix64; entry (r, j) of
 candidate c uses counter (c*s + r)*(n-1) + j) and keeps the candidate with the
 smallest amplification  gamma = max_f sum_i |a_fi| ||b_i||_2 / sqrt(n).
+`design_code` adds the fall-back used when even the best cyclic candidate is
+too badly conditioned for fp32 messages: the fractional-repetition design
+(another published gradient code; needs s+1 | n), whose decode rows are 0/1.
 
 Exact-rational variants (fractions.Fraction) serve the brute-force tests.
 """
@@ -113,8 +116,41 @@ def amplification(B: np.ndarray, A: np.ndarray) -> float:
     return float(np.max(np.abs(A) @ norms) / math.sqrt(n))
 
 
-def search_encoding_matrix(n: int, s: int, seed: int, candidates: int = DEFAULT_CANDIDATES):
-    """Best-of-K construction.  Returns (B, A, gamma, index of the winning candidate)."""
+def candidate_count(n: int, s: int) -> int:
+    """K = min(2048, max(16, 2^20 // C(n,s))): fewer candidates when every one needs many decode rows."""
+    return min(DEFAULT_CANDIDATES, max(16, (1 << 20) // math.comb(n, s)))
+
+
+def fractional_repetition_matrix(n: int, s: int) -> np.ndarray:
+    """s+1 groups of n/(s+1) workers; worker j of every group holds the j-th window of s+1 partitions (unit-norm rows).
+    s stragglers cannot break all s+1 groups, and the members of an intact group sum to the whole."""
+    assert n % (s + 1) == 0
+    per_group = n // (s + 1)
+    B = np.zeros((n, n))
+    for g in range(s + 1):
+        for j in range(per_group):
+            B[g * per_group + j, j * (s + 1):(j + 1) * (s + 1)] = 1.0 / math.sqrt(s + 1)
+    return B
+
+
+def design_code(n: int, s: int, L: int, seed: int):
+    """The code a plan uses by default: best cyclic candidate, unless its rounding amplification over L levels is too
+    large for fp32 messages (gamma^L > 256) and s+1 divides n; then the fractional-repetition design if its gamma is
+    smaller.  Returns (B, A, gamma, candidate) with candidate = -2 for fractional repetition."""
+    B, A, gamma, c = search_encoding_matrix(n, s, seed, candidates=None)
+    if s > 0 and n % (s + 1) == 0 and not (gamma ** L <= 256.0):
+        FR = fractional_repetition_matrix(n, s)
+        A_fr = decoding_matrix(FR, s)
+        g_fr = amplification(FR, A_fr)
+        if g_fr < gamma:
+            return FR, A_fr, g_fr, -2
+    return B, A, gamma, c
+
+
+def search_encoding_matrix(n: int, s: int, seed: int, candidates: int | None = None):
+    """Best-of-K cyclic construction (K from candidate_count unless given).  Returns (B, A, gamma, index of the winning candidate)."""
+    if candidates is None:
+        candidates = candidate_count(n, s)
     if s == 0:
         B = np.eye(n)
         A = np.ones((1, n))

@@ -255,8 +255,8 @@ int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype
         if (m < p->tree.N) { delete p; return fail(CR_E_INVAL, "m must be at least the number of workers"); }
         if (m > (int64_t(1) << 40)) { delete p; return fail(CR_E_INVAL, "m exceeds 2^40"); }
         p->L = L; p->n = n; p->s = s; p->m = m; p->d = d; p->model = model; p->x_dtype = x_dtype;
-        bool ok = B_or_null ? cr::adopt_code(n, s, B_or_null, p->code) : cr::design_code(n, s, seed, p->code);
-        if (!ok) { delete p; return fail(CR_E_INVAL, B_or_null ? "supplied B has the wrong support or does not decode" : "code search found no usable candidate"); }
+        bool ok = B_or_null ? cr::adopt_code(n, s, B_or_null, p->code) : cr::design_code(n, s, L, seed, p->code);
+        if (!ok) { delete p; return fail(CR_E_INVAL, B_or_null ? "supplied B must have s+1 non-zeros per row and per column and decode every straggler set" : "code search found no usable candidate"); }
         cr::allocate(p->tree, s, m, p->code.B.data(), p->own, p->slabs);
         p->node_slab_begin.assign(p->tree.N + 1, 0);
         for (const cr::Slab &sl : p->slabs) p->node_slab_begin[sl.node + 1] += 1;

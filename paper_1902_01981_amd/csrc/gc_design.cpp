@@ -54,41 +54,62 @@ bool solve_square(std::vector<double> &M, std::vector<double> &rhs, int k)
     return true;
 }
 
-// Least-squares solution of the rows x cols system M x = rhs (rows >= cols) by Householder QR.  M row-major, destroyed.
+// Solution of the consistent rows x cols system M x = rhs (rows >= cols) by Householder QR with column pivoting.  Columns that
+// depend on earlier pivots (replicated workers) get a zero coefficient: a basic solution.  M row-major, destroyed.
 bool least_squares(std::vector<double> &M, std::vector<double> &rhs, int rows, int cols, double *x)
 {
+    std::vector<int> perm(cols);
+    for (int c = 0; c < cols; ++c) perm[c] = c;
+    double scale = 0.0;
+    for (double v : M) scale = std::max(scale, std::fabs(v));
+    if (!(scale > 0.0)) return false;
+    int rank = 0;
     for (int c = 0; c < cols; ++c) {
-        double norm = 0.0;
-        for (int r = c; r < rows; ++r) norm += M[r * cols + c] * M[r * cols + c];
-        norm = std::sqrt(norm);
-        if (!(norm > 1e-300)) return false;
-        double alpha = M[c * cols + c] > 0 ? -norm : norm;
+        // pivot: the remaining column with the largest norm below row c
+        int best = c;
+        double best_norm = -1.0;
+        for (int j = c; j < cols; ++j) {
+            double nj = 0.0;
+            for (int r = c; r < rows; ++r) nj += M[r * cols + j] * M[r * cols + j];
+            if (nj > best_norm) { best_norm = nj; best = j; }
+        }
+        if (!(std::sqrt(best_norm) > 1e-12 * scale * rows)) break;
+        if (best != c) {
+            for (int r = 0; r < rows; ++r) std::swap(M[r * cols + best], M[r * cols + c]);
+            std::swap(perm[best], perm[c]);
+        }
+        const double norm = std::sqrt(best_norm);
+        const double alpha = M[c * cols + c] > 0 ? -norm : norm;
         // v = column - alpha e_c, stored in place; beta = 2 / (v.v)
-        double v0 = M[c * cols + c] - alpha;
+        const double v0 = M[c * cols + c] - alpha;
         double vv = v0 * v0;
         for (int r = c + 1; r < rows; ++r) vv += M[r * cols + c] * M[r * cols + c];
-        if (!(vv > 0.0)) { M[c * cols + c] = alpha; continue; }
-        double beta = 2.0 / vv;
-        for (int j = c + 1; j < cols; ++j) {
-            double dot = v0 * M[c * cols + j];
-            for (int r = c + 1; r < rows; ++r) dot += M[r * cols + c] * M[r * cols + j];
+        if (vv > 0.0) {
+            const double beta = 2.0 / vv;
+            for (int j = c + 1; j < cols; ++j) {
+                double dot = v0 * M[c * cols + j];
+                for (int r = c + 1; r < rows; ++r) dot += M[r * cols + c] * M[r * cols + j];
+                dot *= beta;
+                M[c * cols + j] -= dot * v0;
+                for (int r = c + 1; r < rows; ++r) M[r * cols + j] -= dot * M[r * cols + c];
+            }
+            double dot = v0 * rhs[c];
+            for (int r = c + 1; r < rows; ++r) dot += M[r * cols + c] * rhs[r];
             dot *= beta;
-            M[c * cols + j] -= dot * v0;
-            for (int r = c + 1; r < rows; ++r) M[r * cols + j] -= dot * M[r * cols + c];
+            rhs[c] -= dot * v0;
+            for (int r = c + 1; r < rows; ++r) rhs[r] -= dot * M[r * cols + c];
         }
-        double dot = v0 * rhs[c];
-        for (int r = c + 1; r < rows; ++r) dot += M[r * cols + c] * rhs[r];
-        dot *= beta;
-        rhs[c] -= dot * v0;
-        for (int r = c + 1; r < rows; ++r) rhs[r] -= dot * M[r * cols + c];
         M[c * cols + c] = alpha;
+        rank = c + 1;
     }
-    for (int c = cols - 1; c >= 0; --c) {
+    std::vector<double> z(cols, 0.0);
+    for (int c = rank - 1; c >= 0; --c) {
         double v = rhs[c];
-        for (int j = c + 1; j < cols; ++j) v -= M[c * cols + j] * x[j];
-        x[c] = v / M[c * cols + c];
+        for (int j = c + 1; j < rank; ++j) v -= M[c * cols + j] * z[j];
+        z[c] = v / M[c * cols + c];
     }
-    return true;
+    for (int c = 0; c < cols; ++c) x[perm[c]] = z[c];
+    return rank > 0;
 }
 
 // Rows of B from H (s x n): b_i(i) = 1, the other s support entries solve H[:, others] x = -H[:, i]; unit 2-norm.
@@ -193,7 +214,19 @@ uint64_t straggler_set_by_rank(int n, int s, int64_t f)
     return bits;
 }
 
-bool design_code(int n, int s, uint64_t seed, GcCode &out)
+// Fractional repetition: s+1 groups of n/(s+1) workers; worker j of every group holds the j-th window of s+1 partitions
+// (all entries equal, unit 2-norm).  s stragglers cannot break all s+1 groups, and the members of an intact group sum to the whole.
+static void fractional_repetition(int n, int s, std::vector<double> &B)
+{
+    const int per_group = n / (s + 1);
+    B.assign(static_cast<size_t>(n) * n, 0.0);
+    const double v = 1.0 / std::sqrt(static_cast<double>(s + 1));
+    for (int g = 0; g <= s; ++g)
+        for (int j = 0; j < per_group; ++j)
+            for (int t = 0; t <= s; ++t) B[(g * per_group + j) * n + j * (s + 1) + t] = v;
+}
+
+bool design_code(int n, int s, int L, uint64_t seed, GcCode &out)
 {
     out.n = n; out.s = s;
     if (s == 0) {
@@ -224,6 +257,14 @@ bool design_code(int n, int s, uint64_t seed, GcCode &out)
         double g = amplification(B.data(), n, s);
         if (g < best) { best = g; out.B = B; out.candidate = c; }
     }
+    // Fall-back for badly conditioned cyclic codes: when fp32 rounding amplified over L levels, gamma^L 2^-24, would exceed 2^-16
+    // and s+1 divides n, the fractional-repetition design (0/1 decode rows) is used instead if its gamma is smaller.
+    if (n % (s + 1) == 0 && !(std::pow(best, L) <= 256.0)) {
+        std::vector<double> FR;
+        fractional_repetition(n, s, FR);
+        const double g = amplification(FR.data(), n, s);
+        if (g < best) { best = g; out.B = FR; out.candidate = -2; }
+    }
     if (!std::isfinite(best)) return false;
     out.gamma = best;
     return true;
@@ -232,14 +273,19 @@ bool design_code(int n, int s, uint64_t seed, GcCode &out)
 bool adopt_code(int n, int s, const double *B, GcCode &out)
 {
     out.n = n; out.s = s; out.candidate = -1;
-    for (int i = 0; i < n; ++i)
+    // Section II-C: every worker holds s+1 partitions and every partition sits in s+1 workers
+    std::vector<int> per_col(n, 0);
+    for (int i = 0; i < n; ++i) {
+        int per_row = 0;
         for (int j = 0; j < n; ++j) {
-            bool in_support = ((j - i + n) % n) <= s;
-            double v = B[i * n + j];
+            const double v = B[i * n + j];
             if (!std::isfinite(v)) return false;
-            if (!in_support && v != 0.0) return false;
-            if (in_support && v == 0.0) return false;
+            if (v != 0.0) { ++per_row; ++per_col[j]; }
         }
+        if (per_row != s + 1) return false;
+    }
+    for (int j = 0; j < n; ++j)
+        if (per_col[j] != s + 1) return false;
     out.B.assign(B, B + static_cast<size_t>(n) * n);
     out.gamma = amplification(B, n, s);
     return std::isfinite(out.gamma);

@@ -7,9 +7,9 @@ namespace cr {
 
 struct GcCode {
     int n = 0, s = 0;
-    std::vector<double> B;   // n x n row-major; row i supported on {i, ..., i+s} mod n, unit 2-norm, B[i][i] > 0
+    std::vector<double> B;   // n x n row-major; s+1 non-zeros per row and per column, unit 2-norm rows
     double gamma = 0.0;      // max_f sum_i |a_fi| ||b_i||_2 / sqrt(n)
-    int candidate = -1;      // winning candidate of the search, -1 when B was supplied
+    int candidate = -1;      // winning candidate of the search; -1 when B was supplied; -2 for the fractional-repetition design
 };
 
 // Number of straggler sets of size exactly s, C(n,s); returns -1 if it exceeds `limit`.
@@ -20,10 +20,12 @@ int search_candidates(int n, int s);
 
 // Best-of-K design: candidate c draws H (s x n, rows summing to zero) from the splitmix64 stream seeded with `seed`
 // (entry (r,j), j < n-1, uses counter (c*s + r)*(n-1) + j, mapped to [-1,1)); rows of B solve H b_i^T = 0 on the
-// cyclic support.  Keeps the candidate with the smallest gamma.  Returns false if no candidate is usable.
-bool design_code(int n, int s, uint64_t seed, GcCode &out);
+// cyclic support {i..i+s} mod n.  Keeps the candidate with the smallest gamma.  If that gamma is too large for fp32 messages over L
+// levels (gamma^L > 256) and s+1 divides n, the fractional-repetition design is taken instead when its gamma is smaller.
+// Returns false if no candidate is usable.
+bool design_code(int n, int s, int L, uint64_t seed, GcCode &out);
 
-// Adopt a caller-supplied B: checks the cyclic support and that every survivor set decodes; computes gamma.
+// Adopt a caller-supplied B: checks s+1 non-zeros per row and per column and that every survivor set decodes; computes gamma.
 bool adopt_code(int n, int s, const double *B, GcCode &out);
 
 // Decode row for the straggler set given as a bitmask over the n children (exactly s bits set):

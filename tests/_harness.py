@@ -52,7 +52,7 @@ class OraclePath:
 
     def __init__(self, L, n, s, X, y, model, B=None, use_native=False):
         self.L, self.n, self.s, self.X, self.y, self.model = L, n, s, X, y, model
-        self.B = np.asarray(B, dtype=np.float64) if B is not None else gc_code.search_encoding_matrix(n, s, cr.DEFAULT_SEED)[0]
+        self.B = np.asarray(B, dtype=np.float64) if B is not None else gc_code.design_code(n, s, L, cr.DEFAULT_SEED)[0]
         self.own, self.subtree = cr_tree.cr_allocate(L, n, s, X.shape[0], self.B)
         self.slabs = cr_tree.slabs_of(self.own)
         self.native = use_native or X.dtype == np.uint16

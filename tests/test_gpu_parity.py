@@ -102,6 +102,9 @@ CASES = [
     ("deep", 4, 2, 1, 3_000, 520, cr.CR_LOGISTIC, cr.CR_F32, None),
     ("big-team", 2, 3, 1, 700, 16_384, cr.CR_LINEAR, cr.CR_F32, None),            # 1024-thread teams
     ("m-equals-N", 2, 3, 1, 12, 64, cr.CR_LINEAR, cr.CR_F32, None),               # one row per worker
+    ("gc-master-worker", 1, 10, 4, 10_000, 512, cr.CR_LINEAR, cr.CR_F32, None),   # one layer, 10 workers, 4 stragglers (fractional repetition)
+    ("uncoded-master-worker", 1, 10, 0, 10_000, 512, cr.CR_LINEAR, cr.CR_F32, None),
+    ("cr-12x2-s3", 2, 12, 3, 31_200, 320, cr.CR_LOGISTIC, cr.CR_F32, None),       # the paper's (12,2) tree, 156 workers, 3 stragglers per group
 ]
 
 
@@ -184,6 +187,39 @@ def test_aggregation_only():
                     assert rel_l2(M[node], ref) <= 1e-4
     # the decoded vector is the sum of all atoms, whatever the mask
     assert rel_l2(g_dev.cpu().numpy(), atoms.astype(np.float64).sum(0)) <= 1e-4
+    cr.cr_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("s", [1, 3])
+def test_aggregation_only_network_sized(s):
+    """(12,2) tree, 156 workers, vectors of the size of the paper's CNN (117 706 parameters, not a multiple of 4: scalar columns)."""
+    torch = _torch()
+    L, n, d = 2, 12, 117_706
+    m = 156 * 40
+    plan = cr.cr_plan_ex(L, n, s, m, d, model=cr.CR_AGGREGATE_ONLY)
+    ws = cr.Workspace(plan)
+    info = ws.info
+    orc = OraclePath(L, n, s, np.zeros((m, 1), dtype=np.float32), np.zeros(m, dtype=np.float32), cr.CR_LINEAR)
+    assert info.num_slabs == len(orc.slabs) and info.num_workers == 156
+    cuts, member = wl.atoms_of([b for (_, b, _, _) in orc.slabs], [e for (_, _, e, _) in orc.slabs])
+    atoms = wl.atom_vectors(1234 + s, len(cuts) - 1, 0, d)
+    G = np.stack([atoms[idx].sum(axis=0, dtype=np.float32) for idx in member])
+    G_dev = torch.from_numpy(G).cuda()
+    g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
+    ng = [np.zeros(d) for _ in range(156)]
+    for q, (nd, _, _, c) in enumerate(orc.slabs):
+        ng[nd] += float(c) * G[q].astype(np.float64)
+    rng = np.random.default_rng(s)
+    for trial in range(6):
+        mask = wl.draw_mask(rng, L, n, s)
+        cr.cr_load_partial_grads(plan, G_dev)
+        cr.cr_encode_tree(plan, mask)
+        cr.cr_decode_root(plan, g_dev)
+        cr.cr_synchronize(plan)
+        msgs, g_ref = orc.execute(ng, mask)
+        assert rel_l2(g_dev.cpu().numpy(), g_ref) <= 1e-4
+        M = ws.messages().cpu().numpy()
+        assert max(rel_l2(M[node], ref) for node, ref in enumerate(msgs) if ref is not None) <= 1e-4
     cr.cr_plan_destroy(plan)
 
 

@@ -92,6 +92,31 @@ def test_exact_rational_identity(n, s):
     pytest.fail("no non-singular integer H found")
 
 
+@pytest.mark.parametrize("n,s", [(4, 1), (6, 2), (12, 3), (12, 5), (10, 4)])
+def test_fractional_repetition_decodes_every_straggler_set(n, s):
+    B = gc_code.fractional_repetition_matrix(n, s)
+    assert np.all(np.count_nonzero(B, axis=0) == s + 1) and np.all(np.count_nonzero(B, axis=1) == s + 1)
+    A = gc_code.decoding_matrix(B, s)
+    assert np.max(np.abs(A @ B - 1)) <= 1e-12
+    for f, T in enumerate(gc_code.straggler_sets(n, s)):
+        assert all(A[f, j] == 0 for j in T)
+    # pigeonhole: some group of n/(s+1) replicas is intact, so a 0/1 row (times the row norm) always exists
+    per_group = n // (s + 1)
+    for T in gc_code.straggler_sets(n, s):
+        intact = [g for g in range(s + 1) if not any(g * per_group <= j < (g + 1) * per_group for j in T)]
+        assert intact
+        a = np.zeros(n)
+        a[intact[0] * per_group:(intact[0] + 1) * per_group] = np.sqrt(s + 1)
+        np.testing.assert_allclose(a @ B, 1.0, atol=1e-12)
+    assert gc_code.amplification(B, A) <= 2.0 + 1e-9     # all-positive 0/1-like rows: no cancellation to amplify
+
+
+def test_candidate_count_rule():
+    assert gc_code.candidate_count(3, 1) == 2048 and gc_code.candidate_count(12, 3) == 2048
+    assert gc_code.candidate_count(12, 5) == (1 << 20) // 792 and gc_code.candidate_count(20, 5) == 67
+    assert gc_code.candidate_count(24, 12) == 16
+
+
 def test_zero_stragglers_is_identity():
     B, A, gamma, _ = gc_code.search_encoding_matrix(5, 0, seed=1)
     assert np.array_equal(B, np.eye(5)) and np.array_equal(A, np.ones((1, 5)))

@@ -60,7 +60,7 @@ def test_default_code_matches_the_oracle_search(plans, L, n, s, m, d):
 def test_allocation_matches_the_oracle(plans, L, n, s, m, d):
     model = cr.CR_AGGREGATE_ONLY if d > 100_000 else cr.CR_LINEAR
     p = plans(L, n, s, m, d, model=model)
-    own, _ = cr_tree.cr_allocate(L, n, s, m, gc_code.search_encoding_matrix(n, s, cr.DEFAULT_SEED)[0])
+    own, _ = cr_tree.cr_allocate(L, n, s, m, gc_code.design_code(n, s, L, cr.DEFAULT_SEED)[0])
     expect = cr_tree.slabs_of(own)
     node, rb, re_, coef = cr.cr_plan_get_slabs(p)
     assert len(expect) == len(node)
@@ -69,6 +69,34 @@ def test_allocation_matches_the_oracle(plans, L, n, s, m, d):
     info = cr.cr_plan_info(p)
     rows = [cr_tree.set_size(o) for o in own]
     assert (info.row_visits, info.min_rows, info.max_rows) == (sum(rows), min(rows), max(rows))
+
+
+@pytest.mark.parametrize("L,n,s", [(2, 12, 2), (2, 12, 3), (2, 12, 5), (1, 10, 4), (2, 6, 1), (2, 12, 1)])
+def test_fall_back_to_fractional_repetition(plans, L, n, s):
+    """Wide groups: the best cyclic code is too badly conditioned for fp32 messages; both sides switch to the 0/1 design."""
+    p = plans(L, n, s, 40 * cr_tree.num_workers(n, L), 16)
+    info = cr.cr_plan_info(p)
+    Bo, Ao, gamma, cand = gc_code.design_code(n, s, L, cr.DEFAULT_SEED)
+    assert info.code_candidate == cand
+    B = cr.cr_plan_get_B(p)
+    np.testing.assert_allclose(B, Bo, atol=1e-12)
+    assert info.gamma == pytest.approx(gamma, rel=1e-9)
+    A = cr.cr_plan_get_A(p)
+    assert np.max(np.abs(A @ B - 1)) <= 1e-10
+    for f, T in enumerate(gc_code.straggler_sets(n, s)):
+        assert all(A[f, j] == 0 for j in T)
+    if cand == -2:
+        assert info.gamma <= 2.0 + 1e-12 and gamma ** L <= 256
+        assert np.all(np.count_nonzero(B, axis=0) == s + 1) and np.all(np.count_nonzero(B, axis=1) == s + 1)
+        cyc = gc_code.search_encoding_matrix(n, s, cr.DEFAULT_SEED)[2]
+        assert cyc ** L > 256                             # the rule that triggered the fall-back
+    else:
+        assert gamma ** L <= 256 or n % (s + 1) != 0
+    own, _ = cr_tree.cr_allocate(L, n, s, info.m, Bo)     # allocation follows whichever code was chosen
+    node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+    expect = cr_tree.slabs_of(own)
+    assert [e[:3] for e in expect] == list(zip(node.tolist(), rb.tolist(), re_.tolist()))
+    np.testing.assert_allclose(coef, [e[3] for e in expect], rtol=1e-11)
 
 
 def test_printed_example_through_the_plan(plans, golden_dir):
@@ -146,7 +174,7 @@ def test_argument_errors(plans):
             plans(*args)
         assert ei.value.status == cr.CR_E_INVAL, args
     with pytest.raises(cr.CodedReduceError):
-        plans(2, 3, 1, 100, 4, B=np.eye(3))             # wrong support for s = 1
+        plans(2, 3, 1, 100, 4, B=np.eye(3))             # one partition per worker cannot survive a straggler
     with pytest.raises(cr.CodedReduceError):
         plans(2, 3, 1, 100, 30_000)                     # beyond the single-pass kernels
     p = plans(2, 3, 1, 100, 4)
