@@ -2,7 +2,8 @@
 """Benchmark of the CodedReduce hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
-host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> cr_gd_update.
+host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> cr_gd_update
+(issued through cr_gd_run, which enqueues exactly these calls for every step).
 Prints ONE JSON line: iterations/s, the roofline of the dominant kernel (measured live with HIP events on the
 library's stream) and the CPU oracle timed on a bounded sample of the same workload.
 
@@ -29,6 +30,8 @@ DESCRIPTIONS = {
     "cfg3": "CR tree L=3 n=4 s=1 (84 workers), logistic regression fp32, m=252000 d=4096, random mask per step",
     "cfg4": "aggregation only: CR tree L=2 n=8 s=2 (72 workers), 248 fp32 partition-gradient vectors of length 2^24, encode+decode",
     "cfg5": "CR tree L=3 n=6 s=2 (258 workers), linear regression, X bf16 / fp32 accumulate, m=2064000 d=1024, random mask per step",
+    "gc20": "one-layer gradient coding, n=20 s=4 (same data and resiliency as cfg2), linear regression fp32, m=100000 d=10000",
+    "umw20": "uncoded master-worker, n=20 s=0 (same data as cfg2), linear regression fp32, m=100000 d=10000",
     "nn12": "aggregation only: CR tree L=2 n=12 s=3 (156 workers), fp32 partition-gradient vectors of length 117706 (network sized), encode+decode",
 }
 
@@ -152,24 +155,28 @@ def main() -> int:
     rng = wl.mask_stream(cfg)
     lr = float(cfg["lr"])
 
-    def step(mask):
-        if aggregate:
-            cr.cr_load_partial_grads(plan, G_dev)
-        else:
-            cr.cr_partial_grads(plan, X_dev, y_dev, w_dev)
-        cr.cr_encode_tree(plan, mask)
-        cr.cr_decode_root(plan, g_dev)
-        if not aggregate:
-            cr.cr_gd_update(plan, w_dev, g_dev, lr)
+    def run(steps):
+        # host-drawn straggler masks, then the whole path; for regression workloads the gradient-descent loop is a library call
+        # that enqueues its steps without waiting for the device, so the masks of the next batch are drawn while this one runs
+        done = 0
+        while done < steps:
+            batch = min(8, steps - done)
+            masks = np.stack([wl.draw_mask(rng, L, n, s) for _ in range(batch)])
+            if aggregate:
+                for mask in masks:
+                    cr.cr_load_partial_grads(plan, G_dev)
+                    cr.cr_encode_tree(plan, mask)
+                    cr.cr_decode_root(plan, g_dev)
+            else:
+                cr.cr_gd_run(plan, X_dev, y_dev, w_dev, g_dev, masks, lr)
+            done += batch
 
-    for _ in range(args.warmup):
-        step(wl.draw_mask(rng, L, n, s))
+    run(args.warmup)
     torch.cuda.synchronize()
     cr.cr_profile_enable(plan, True)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for _ in range(args.steps):
-        step(wl.draw_mask(rng, L, n, s))
+    run(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     kernels = {}

@@ -30,6 +30,10 @@ CONFIGS = {
     # the paper's simulated network training: (12,2) tree, 156 workers, about 120 000 parameters (5 layers: 3x16x3x3, 16x64x4x4,
     # 64x384, 384x192, 192x10 weights plus biases = 117 706), aggregation only
     "nn12": dict(L=2, n=12, s=3, m=156 * 40, d=117_706, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
+    # configuration 2's data with 20 workers under one master instead of a (4,2) tree: gradient coding with the same resiliency
+    # (4 of 20 = 1 of 4 children may straggle) and the uncoded split.  Section III-C compares their computation loads.
+    "gc20": dict(L=1, n=20, s=4, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
+    "umw20": dict(L=1, n=20, s=0, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
     "cfg5": dict(L=3, n=6, s=2, m=2_064_000, d=1_024, model=LINEAR, x_dtype=BF16, noise=0.01, steps=100, lr=4e-7, w0_std=1.0),
 }
 
@@ -37,7 +41,7 @@ CONFIGS = {
 def config(name: str, **overrides) -> dict:
     cfg = dict(CONFIGS[name])
     cfg["name"] = name
-    cfg["seed"] = BASE_SEED + (int(name[3:]) if name.startswith("cfg") else 12)
+    cfg["seed"] = BASE_SEED + {"nn12": 12, "gc20": 2, "umw20": 2}.get(name, int(name[3:]) if name.startswith("cfg") else 0)
     cfg.update(overrides)
     return cfg
 
@@ -123,10 +127,12 @@ def num_workers(n: int, L: int) -> int:
 def draw_mask(rng: np.random.Generator, L: int, n: int, s: int) -> np.ndarray:
     """Exactly s stragglers in every sibling group, each size-s subset equally likely."""
     N = num_workers(n, L)
-    mask = np.zeros(N, dtype=np.uint8)
-    for g in range(N // n):
-        mask[g * n + rng.choice(n, size=s, replace=False)] = 1
-    return mask
+    mask = np.zeros((N // n, n), dtype=np.uint8)
+    if s > 0:
+        # the s smallest of n i.i.d. uniforms sit at a uniformly random size-s subset
+        pick = np.argpartition(rng.random((N // n, n)), s - 1, axis=1)[:, :s]
+        np.put_along_axis(mask, pick, 1, axis=1)
+    return mask.reshape(N)
 
 
 def mask_stream(cfg: dict) -> np.random.Generator:

@@ -111,6 +111,18 @@ int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
 /* pieces in execution order: piece i is rows [row_begin[i], row_end[i]) of slab[i], run by team[i]; num_pieces entries each, any may be NULL */
 int cr_plan_get_pieces(const cr_plan_t *plan, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team);
 
+/* ---- run-time model (host only; Section III-C "Latency Performance", eq. (5), Theorem 2) ------------------------------------
+ * Simulates iteration number `iteration` of the plan's tree: worker k, holding rows_k data points, computes for
+ * a*rows_k + (rows_k/mu) * Exp(1) (the shifted-exponential law of eq. (5), drawn from the counter-based splitmix64 stream seeded
+ * with `seed`, counter iteration*N + k); a parent receives one message at a time, in order of readiness, t_c per message, and
+ * decodes after n-s of them; all nodes compute from time 0 and while receiving.
+ *   mask   host, N bytes or NULL: 1 for the s children of every group that were not waited for (usable by cr_encode_tree)
+ *   ready  host, N doubles or NULL: time each node's message is ready to send
+ *   total  host or NULL: time at which the master has decoded
+ * CR_E_INVAL unless a >= 0, mu > 0, t_c >= 0, iteration >= 0. */
+int cr_simulate_iteration(const cr_plan_t *plan, double a, double mu, double t_c, uint64_t seed, int64_t iteration,
+                          uint8_t *mask, double *ready, double *total);
+
 /* ---- device binding --------------------------------------------------------------------------------------------
  * The workspace holds the device tables, the per-call encode program, the stage-1 piece partials, the slab gradients
  * G[S][d] (not for CR_AGGREGATE_ONLY) and the messages M[N][d], all fp32 rows of d floats.  dev_ptr must be 256-byte aligned and stay valid while the plan
@@ -136,6 +148,16 @@ int cr_load_partial_grads(cr_plan_t *plan, const float *G_dev);
 int cr_encode_tree(cr_plan_t *plan, const uint8_t *straggler_mask_host);
 int cr_decode_root(cr_plan_t *plan, float *g_dev);
 int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
+
+/* Gradient descent loop kept on the device (eq. (2) with a plain step): `steps` times  g = CodedReduce(w);  w <- w - lr g,  enqueued
+ * back to back with no host synchronisation beyond the staging ring of the encode programs (the host runs at most 4 steps ahead).
+ *   masks_host      steps x N bytes, one straggler mask per step; all are checked first: CR_E_UNDECODABLE before anything is enqueued
+ *   w_dev, g_dev    d floats each; w is updated in place, g holds the last decoded gradient
+ *   w_star_or_null  d floats (device): the reference model of the normalised error rate, or NULL
+ *   metrics_or_null device, steps x 2 floats: [2t] = ||w_t+1 - w_t||^2 / ||w_t||^2 (relative error rate, eq. (6)),
+ *                   [2t+1] = ||w_t+1 - w*||^2 / ||w*||^2 (normalised error rate, eq. (8); -1 without w*); NULL = plain update */
+int cr_gd_run(cr_plan_t *plan, const void *X_dev, const float *y_dev, float *w_dev, float *g_dev, const uint8_t *masks_host,
+              int steps, float lr, const float *w_star_or_null, float *metrics_or_null);
 
 /* ---- results kept in the workspace (device pointers, valid while the workspace is) --------------------------- */
 int cr_get_slab_grads(const cr_plan_t *plan, const float **G_dev); /* S x d */

@@ -24,8 +24,8 @@ DEFAULT_SEED = 190201981
 
 EXPORTS = [
     "cr_plan", "cr_plan_ex", "cr_plan_destroy", "cr_plan_info", "cr_plan_get_B", "cr_plan_get_A", "cr_plan_get_slabs",
-    "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_workspace_bytes", "cr_bind_workspace",
-    "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_get_slab_grads",
+    "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
+    "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
 ]
 
@@ -66,6 +66,8 @@ def load_library():
         lib.cr_plan_decode_row.argtypes = [vp, vp, vp]
         lib.cr_plan_set_split.argtypes = [vp, c_int, i64]
         lib.cr_plan_get_pieces.argtypes = [vp, vp, vp, vp, vp]
+        lib.cr_simulate_iteration.argtypes = [vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_uint64, i64, vp, vp,
+                                              ctypes.POINTER(ctypes.c_double)]
         lib.cr_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         lib.cr_bind_workspace.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.cr_partial_grads.argtypes = [vp, vp, vp, vp]
@@ -73,6 +75,7 @@ def load_library():
         lib.cr_encode_tree.argtypes = [vp, vp]
         lib.cr_decode_root.argtypes = [vp, vp]
         lib.cr_gd_update.argtypes = [vp, vp, vp, ctypes.c_float]
+        lib.cr_gd_run.argtypes = [vp, vp, vp, vp, vp, vp, c_int, ctypes.c_float, vp, vp]
         lib.cr_get_slab_grads.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_get_messages.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_profile_enable.argtypes = [vp, c_int]
@@ -175,6 +178,16 @@ def cr_plan_get_pieces(plan: int):
     return slab, rb, re, team
 
 
+def cr_simulate_iteration(plan: int, a: float, mu: float, t_c: float, seed: int, iteration: int):
+    """Returns (mask uint8[N], ready float64[N], total)."""
+    N = cr_plan_info(plan).num_workers
+    mask = np.zeros(N, dtype=np.uint8)
+    ready = np.zeros(N, dtype=np.float64)
+    total = ctypes.c_double()
+    _check(load_library().cr_simulate_iteration(plan, a, mu, t_c, seed, iteration, mask.ctypes.data, ready.ctypes.data, ctypes.byref(total)))
+    return mask, ready, total.value
+
+
 # ---- device binding and the hot path --------------------------------------------------------------------------------
 def cr_workspace_bytes(plan: int) -> int:
     out = ctypes.c_size_t()
@@ -207,6 +220,13 @@ def cr_decode_root(plan: int, g) -> None:
 
 def cr_gd_update(plan: int, w, g, lr: float) -> None:
     _check(load_library().cr_gd_update(plan, _ptr(w), _ptr(g), lr))
+
+
+def cr_gd_run(plan: int, X, y, w, g, masks, lr: float, w_star=None, metrics=None) -> None:
+    m = np.ascontiguousarray(masks, dtype=np.uint8)
+    if m.ndim != 2 or m.shape[1] != cr_plan_info(plan).num_workers:
+        raise ValueError("masks must be steps x N bytes")
+    _check(load_library().cr_gd_run(plan, _ptr(X), _ptr(y), _ptr(w), _ptr(g), m.ctypes.data, m.shape[0], lr, _ptr(w_star), _ptr(metrics)))
 
 
 def cr_get_slab_grads(plan: int) -> int:

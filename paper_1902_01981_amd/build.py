@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodedreduce.so")
-SOURCES = ["gc_design.cpp", "tree_plan.cpp", "codedreduce.cpp", "kernels.hip"]
+SOURCES = ["gc_design.cpp", "tree_plan.cpp", "latency_model.cpp", "codedreduce.cpp", "kernels.hip"]
 # the packed-fp32 target feature is switched off for all device code
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

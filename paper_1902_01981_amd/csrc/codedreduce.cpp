@@ -15,6 +15,7 @@
 
 #include "gc_design.h"
 #include "kernels.h"
+#include "latency_model.h"
 #include "tree_plan.h"
 
 namespace {
@@ -382,6 +383,18 @@ int cr_plan_get_pieces(const cr_plan_t *p, int32_t *slab, int64_t *row_begin, in
     return CR_OK;
 }
 
+int cr_simulate_iteration(const cr_plan_t *p, double a, double mu, double t_c, uint64_t seed, int64_t iteration, uint8_t *mask,
+                          double *ready, double *total)
+{
+    if (!p) return fail(CR_E_INVAL, "NULL plan");
+    if (!(a >= 0.0) || !(mu > 0.0) || !(t_c >= 0.0) || iteration < 0) return fail(CR_E_INVAL, "a >= 0, mu > 0, t_c >= 0, iteration >= 0 required");
+    std::vector<int64_t> rows(p->tree.N, 0);
+    for (const cr::Slab &sl : p->slabs) rows[sl.node] += sl.row_end - sl.row_begin;
+    const double t = cr::simulate_iteration(p->tree, p->s, rows, {a, mu, t_c}, seed, iteration, mask, ready);
+    if (total) *total = t;
+    return CR_OK;
+}
+
 int cr_workspace_bytes(cr_plan_t *p, size_t *bytes)
 {
     if (!p || !bytes) return fail(CR_E_INVAL, "NULL argument");
@@ -591,6 +604,39 @@ int cr_gd_update(cr_plan_t *p, float *w, const float *g, float lr)
     LaunchTimer t(p, CR_K_UPDATE, 3 * p->d * 4);
     CR_HIP(cr::launch_update(w, g, lr, p->d, p->stream));
     t.done();
+    return CR_OK;
+}
+
+int cr_gd_run(cr_plan_t *p, const void *X, const float *y, float *w, float *g, const uint8_t *masks, int steps, float lr,
+              const float *w_star, float *metrics)
+{
+    if (!p || !X || !y || !w || !g || !masks) return fail(CR_E_INVAL, "NULL argument");
+    if (steps < 0) return fail(CR_E_INVAL, "steps must be >= 0");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_STATE, "aggregation-only plan has no gradient stage");
+    const int n = p->n;
+    const int32_t N = p->tree.N;
+    for (int t = 0; t < steps; ++t)                     // every mask is checked before anything is enqueued
+        for (int32_t grp = 0; grp < N / n; ++grp) {
+            int cnt = 0;
+            for (int j = 0; j < n; ++j) cnt += masks[static_cast<size_t>(t) * N + static_cast<size_t>(grp) * n + j] ? 1 : 0;
+            if (cnt > p->s)
+                return fail(CR_E_UNDECODABLE, "step " + std::to_string(t) + ": sibling group " + std::to_string(grp) + " has more than s stragglers");
+        }
+    for (int t = 0; t < steps; ++t) {
+        int rc = cr_partial_grads(p, X, y, w);
+        if (rc == CR_OK) rc = cr_encode_tree(p, masks + static_cast<size_t>(t) * N);
+        if (rc == CR_OK) rc = cr_decode_root(p, g);
+        if (rc != CR_OK) return rc;
+        if (metrics) {
+            LaunchTimer tm(p, CR_K_UPDATE, 3 * p->d * 4 + (w_star ? p->d * 4 : 0));
+            CR_HIP(cr::launch_update_metrics(w, g, lr, w_star, metrics + 2 * static_cast<size_t>(t), p->d, p->stream));
+            tm.done();
+        } else {
+            rc = cr_gd_update(p, w, g, lr);
+            if (rc != CR_OK) return rc;
+        }
+    }
     return CR_OK;
 }
 

@@ -53,5 +53,6 @@ hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_
 hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream);
 hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream);
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream);
+hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream);
 
 }  // namespace cr

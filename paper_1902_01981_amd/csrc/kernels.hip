@@ -351,6 +351,45 @@ __global__ void __launch_bounds__(256) update_kernel(float *__restrict__ w, cons
     if (i < d) w[i] = fmaf(-lr, g[i], w[i]);
 }
 
+// Gradient step fused with the two convergence measures of the paper's experiments: metrics[0] = ||w_new - w||^2 / ||w||^2
+// (relative error rate, eq. (6)), metrics[1] = ||w_new - w*||^2 / ||w*||^2 (normalised error rate, eq. (8)), or -1 without w*.
+// One workgroup, fixed summation order: the model has at most a few 10^4 entries on this path.
+__global__ void __launch_bounds__(1024)
+update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float lr, const float *__restrict__ w_star,
+                      float *__restrict__ metrics, int64_t d)
+{
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};   // |dw|^2, |w|^2, |w_new - w*|^2, |w*|^2
+    for (int64_t i = threadIdx.x; i < d; i += 1024) {
+        const float wo = w[i];
+        const float wn = fmaf(-lr, g[i], wo);
+        w[i] = wn;
+        const double dw = static_cast<double>(wn) - static_cast<double>(wo);
+        acc[0] += dw * dw;
+        acc[1] += static_cast<double>(wo) * wo;
+        if (w_star) {
+            const double ws = w_star[i], e = static_cast<double>(wn) - ws;
+            acc[2] += e * e;
+            acc[3] += ws * ws;
+        }
+    }
+    __shared__ double part[16][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+    }
+    if ((threadIdx.x & 63) == 0)
+        for (int k = 0; k < 4; ++k) part[threadIdx.x / 64][k] = acc[k];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int wv = 0; wv < 16; ++wv)
+            for (int k = 0; k < 4; ++k) tot[k] += part[wv][k];
+        metrics[0] = static_cast<float>(tot[0] / tot[1]);
+        metrics[1] = w_star ? static_cast<float>(tot[2] / tot[3]) : -1.f;
+    }
+}
+
 // ---- variant table for stage 1 --------------------------------------------------------------------------------------
 #define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
@@ -452,6 +491,12 @@ hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nte
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream)
 {
     update_kernel<<<static_cast<unsigned>((d + 255) / 256), 256, 0, stream>>>(w, g, lr, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream)
+{
+    update_metrics_kernel<<<1, 1024, 0, stream>>>(w, g, lr, w_star, metrics, d);
     return hipGetLastError();
 }
 

@@ -146,6 +146,56 @@ def test_gd_trajectory_cfg1():
     hip.close()
 
 
+def test_device_resident_gd_loop_and_run_time_model_masks():
+    """cr_gd_run against the step-by-step calls (bit-identical models) and against uncoded fp64 GD; masks come from the
+    run-time model (the s slowest children of every group under shifted-exponential compute times)."""
+    torch = _torch()
+    cfg = wl.config("cfg1")
+    data = wl.make_dataset(cfg)
+    L, n, s = cfg["L"], cfg["n"], cfg["s"]
+    hip = HipPath(L, n, s, data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(L, n, s, data["X"], data["y"], cr.CR_LINEAR)
+    steps, lr = 12, 2e-4
+    masks = np.stack([cr.cr_simulate_iteration(hip.plan, 5e-5, 2e4, 0.05, 42, t)[0] for t in range(steps)])
+    assert all(masks[t, g * n:(g + 1) * n].sum() == s for t in range(steps) for g in range(4)) and len({m.tobytes() for m in masks}) > 1
+    # step by step
+    w_a = torch.from_numpy(data["w0"]).cuda()
+    for t in range(steps):
+        hip.gradient(w_a, masks[t])
+        cr.cr_gd_update(hip.plan, w_a, hip.g, lr)
+    # one call, with the convergence measures
+    w_b = torch.from_numpy(data["w0"]).cuda()
+    w_star = torch.from_numpy(data["w_star"]).cuda()
+    metrics = torch.zeros(steps, 2, dtype=torch.float32, device="cuda")
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_b, hip.g, masks, lr, w_star, metrics)
+    cr.cr_synchronize(hip.plan)
+    assert torch.equal(w_a, w_b)
+    # and without them (plain update kernel)
+    w_c = torch.from_numpy(data["w0"]).cuda()
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_c, hip.g, masks, lr)
+    cr.cr_synchronize(hip.plan)
+    assert torch.equal(w_a, w_c)
+    # uncoded fp64 gradient descent (the oracle) gives the same trajectory and the same measures
+    w = data["w0"].astype(np.float64)
+    ws = data["w_star"].astype(np.float64)
+    ref = []
+    for t in range(steps):
+        w_new = w - lr * orc.full_gradient(w)
+        ref.append([np.sum((w_new - w) ** 2) / np.sum(w ** 2), np.sum((w_new - ws) ** 2) / np.sum(ws ** 2)])
+        w = w_new
+    assert rel_l2(w_b.cpu().numpy(), w) <= 1e-5
+    np.testing.assert_allclose(metrics.cpu().numpy(), np.array(ref), rtol=2e-3)
+    assert np.all(np.diff(metrics.cpu().numpy()[:, 1]) < 0)            # normalised error rate falls
+    bad = masks.copy()
+    bad[5, 3:5] = 1
+    with pytest.raises(cr.CodedReduceError) as ei:
+        cr.cr_gd_run(hip.plan, hip.X, hip.y, w_c, hip.g, bad, lr)
+    assert ei.value.status == cr.CR_E_UNDECODABLE
+    cr.cr_synchronize(hip.plan)
+    assert torch.equal(w_a, w_c)                         # nothing was enqueued
+    hip.close()
+
+
 def test_aggregation_only():
     """Partition gradients supplied as vectors (L=2, n=8, s=2): encode + decode alone, 20 masks."""
     torch = _torch()

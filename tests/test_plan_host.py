@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "codedreduce.h")) as f:
         header = f.read()
     declared = set(re.findall(r"^(?:int|void|const char \*)\s*\**(cr_\w+)\(", header, flags=re.M))
-    assert declared == set(cr.EXPORTS) and len(declared) == 24
+    assert declared == set(cr.EXPORTS) and len(declared) == 26
     lib = ctypes.CDLL(cr.LIB_PATH)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -164,6 +164,25 @@ def test_row_cell_split(plans, cell_rows):
         cr.cr_plan_set_split(p, 7, 5)
     with pytest.raises(cr.CodedReduceError):
         cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, 0)
+
+
+@pytest.mark.parametrize("L,n,s,m", [(2, 3, 1, 1200), (1, 12, 3, 5000), (3, 4, 1, 25_200), (2, 12, 5, 49_920)])
+def test_run_time_model_matches_the_oracle(plans, L, n, s, m):
+    from oracle import latency
+
+    p = plans(L, n, s, m, 8)
+    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    rows = np.bincount(node, weights=(re_ - rb), minlength=cr.cr_plan_info(p).num_workers).astype(np.int64)
+    a, mu, t_c = 5e-5, 2e4, 0.05                          # the constants of the paper's simulated network experiment
+    for it in [0, 1, 7, 1000]:
+        mask, ready, total = cr.cr_simulate_iteration(p, a, mu, t_c, 99, it)
+        omask, oready, ototal = latency.simulate(L, n, s, [int(r) for r in rows], a, mu, t_c, 99, it)
+        assert list(mask) == omask
+        np.testing.assert_allclose(ready, oready, rtol=1e-12)
+        assert total == pytest.approx(ototal, rel=1e-12)
+        assert all(mask[g * n:(g + 1) * n].sum() == s for g in range(len(mask) // n))
+    with pytest.raises(cr.CodedReduceError):
+        cr.cr_simulate_iteration(p, a, 0.0, t_c, 1, 0)
 
 
 def test_argument_errors(plans):
