@@ -132,6 +132,18 @@ int ensure_split(cr_plan_t *p)
     if (!p->variant) return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels");
     int kind = p->split_kind;
     int64_t value = p->split_value;
+    if (kind < 0 && p->s == 0) {
+        // no redundancy (every row has one holder): nothing to share, so one contiguous range per resident workgroup streams best
+        int dev = 0, cus = 0, per_cu = 0;
+        int slots = 2 * 256;                                // MI355X: 256 CUs, two resident workgroups each; refined if a device is present
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn, p->variant->block(), 0) == hipSuccess && cus > 0 && per_cu > 0)
+            slots = cus * per_cu;
+        else
+            (void)hipGetLastError();                        // no device: keep the default and clear the error
+        kind = CR_SPLIT_EQUAL_RANGES;
+        value = static_cast<int64_t>(slots) * p->variant->teams_per_block();
+    }
     if (kind < 0) {
         // default: row cells of about 2 MB of X, between 96 and 512 rows, a multiple of 32.  Long enough that the d-float partial
         // row each piece writes is about a percent of what it reads, short enough that the holders of a cell stay in step and
