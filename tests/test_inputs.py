@@ -48,3 +48,13 @@ def test_atoms():
     v = wl.atom_vectors(5, 3, 0, 1000)
     v2 = wl.atom_vectors(5, 3, 0, 1000)
     assert np.array_equal(v, v2) and v.shape == (3, 1000) and abs(v.std() - 1) < 0.1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2 and "one GPU" in res.stderr and res.stdout.strip() == ""
