@@ -185,6 +185,27 @@ def test_run_time_model_matches_the_oracle(plans, L, n, s, m):
         cr.cr_simulate_iteration(p, a, 0.0, t_c, 1, 0)
 
 
+@pytest.mark.parametrize("d,x_dtype,teams_per_group", [(10_000, 0, 1), (4_096, 0, 1), (1_024, 1, 4)])
+def test_holders_of_a_cell_share_an_l2_domain(plans, d, x_dtype, teams_per_group):
+    """Workgroups are dealt round-robin to 8 L2 domains: every holder of a row cell must sit on a workgroup id with the same residue."""
+    p = plans(3, 3, 1, 39_000, d, x_dtype=x_dtype)
+    cell = 128
+    cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, cell)
+    slab, pb, pe, team = cr.cr_plan_get_pieces(p)
+    group = team // teams_per_group                       # workgroup id (256 threads: one 256-thread team or four wavefront teams)
+    cells = pb // cell
+    assert np.all((pe - 1) // cell == cells)
+    multiplicity = []
+    for c in np.unique(cells):
+        g = group[cells == c]
+        assert len(set(g % 8)) == 1, c
+        multiplicity.append(len(g))
+    assert max(multiplicity) >= 8 and min(multiplicity) >= 2      # up to (s+1)^L holders per row (more pieces where a cell straddles slabs)
+    # cells are visited in row order, eight at a time
+    first_team = np.array([team[cells == c].min() for c in np.unique(cells)])
+    assert np.all(np.diff(first_team[::8]) > 0)
+
+
 def test_argument_errors(plans):
     bad = [(0, 3, 1, 100, 4), (9, 2, 1, 10_000, 4), (2, 1, 0, 100, 4), (2, 65, 1, 10 ** 6, 4), (2, 3, 3, 100, 4), (2, 3, -1, 100, 4),
            (2, 3, 1, 11, 4), (2, 3, 1, 100, 0), (2, 40, 20, 10 ** 6, 4)]
