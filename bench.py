@@ -32,6 +32,7 @@ DESCRIPTIONS = {
     "cfg5": "CR tree L=3 n=6 s=2 (258 workers), linear regression, X bf16 / fp32 accumulate, m=2064000 d=1024, random mask per step",
     "gc20": "one-layer gradient coding, n=20 s=4 (same data and resiliency as cfg2), linear regression fp32, m=100000 d=10000",
     "umw20": "uncoded master-worker, n=20 s=0 (same data as cfg2), linear regression fp32, m=100000 d=10000",
+    "paper84": "the paper's linear-regression experiment: CR tree L=3 n=4 s=1 (84 workers), fp32, m=7644 d=6500, noise N(0,1)",
     "nn12": "aggregation only: CR tree L=2 n=12 s=3 (156 workers), fp32 partition-gradient vectors of length 117706 (network sized), encode+decode",
 }
 
@@ -192,6 +193,9 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["algorithmic_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS, "traffic": load_traffic(args.workload),
                 "avg_kernel_ms": dk["avg_ms"], "algorithmic_bytes_per_launch": dk["algorithmic_bytes_per_launch"]}
+    if roofline["traffic"]:
+        # what HBM really moved (rocprofv3 counters of an earlier run of this workload), as a rate over this run's kernel time
+        roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9
 
     # ---- CPU baseline: the oracle on the host cores, same inputs, bounded; also a parity check of one more GPU iteration
     baseline, parity = None, None

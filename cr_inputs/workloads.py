@@ -34,6 +34,8 @@ CONFIGS = {
     # (4 of 20 = 1 of 4 children may straggle) and the uncoded split.  Section III-C compares their computation loads.
     "gc20": dict(L=1, n=20, s=4, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
     "umw20": dict(L=1, n=20, s=0, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
+    # the paper's own linear-regression experiment: 84 workers as a (4,3) tree, one straggler in four, (d,p) = (7644, 6500)
+    "paper84": dict(L=3, n=4, s=1, m=7_644, d=6_500, model=LINEAR, x_dtype=F32, noise=1.0, steps=300, lr=2e-5, w0_std=1.0),
     "cfg5": dict(L=3, n=6, s=2, m=2_064_000, d=1_024, model=LINEAR, x_dtype=BF16, noise=0.01, steps=100, lr=4e-7, w0_std=1.0),
 }
 
@@ -41,7 +43,7 @@ CONFIGS = {
 def config(name: str, **overrides) -> dict:
     cfg = dict(CONFIGS[name])
     cfg["name"] = name
-    cfg["seed"] = BASE_SEED + {"nn12": 12, "gc20": 2, "umw20": 2}.get(name, int(name[3:]) if name.startswith("cfg") else 0)
+    cfg["seed"] = BASE_SEED + {"nn12": 12, "gc20": 2, "umw20": 2, "paper84": 84}.get(name, int(name[3:]) if name.startswith("cfg") else 0)
     cfg.update(overrides)
     return cfg
 

@@ -151,6 +151,8 @@ int ensure_split(cr_plan_t *p)
         kind = CR_SPLIT_ROW_CELLS;
         const int64_t row_bytes = p->d * elem_size(p);
         value = std::min<int64_t>(512, std::max<int64_t>(96, ((int64_t(2) << 20) / row_bytes + 16) / 32 * 32));
+        // small problems: shorter cells, so that there are a few thousand pieces to spread over the chip
+        value = std::min<int64_t>(value, std::max<int64_t>(16, (p->row_visits / 2048 + 15) / 16 * 16));
     }
     if (kind == CR_SPLIT_ROW_CELLS) {
         if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
