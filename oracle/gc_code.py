@@ -155,6 +155,11 @@ def search_encoding_matrix(n: int, s: int, seed: int, candidates: int | None = N
         B = np.eye(n)
         A = np.ones((1, n))
         return B, A, amplification(B, A), 0
+    if s == n - 1:
+        # every worker holds every partition: null(H) is the line through the all-ones vector, all candidates coincide
+        B = np.full((n, n), 1.0 / math.sqrt(n))
+        A = decoding_matrix(B, s)
+        return B, A, amplification(B, A), 0
     sets = straggler_sets(n, s)
     surv = np.array([[i for i in range(n) if i not in T] for T in sets])  # F x (n-s)
     ones = np.ones(n)

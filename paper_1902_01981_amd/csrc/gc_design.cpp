@@ -236,6 +236,13 @@ bool design_code(int n, int s, int L, uint64_t seed, GcCode &out)
         out.candidate = 0;
         return true;
     }
+    if (s == n - 1) {
+        // every worker holds every partition (null(H) is spanned by the all-ones vector): all candidates coincide
+        out.B.assign(static_cast<size_t>(n) * n, 1.0 / std::sqrt(static_cast<double>(n)));
+        out.gamma = amplification(out.B.data(), n, s);
+        out.candidate = 0;
+        return true;
+    }
     const int K = search_candidates(n, s);
     std::vector<double> H(static_cast<size_t>(s) * n), B;
     double best = std::numeric_limits<double>::infinity();

@@ -222,3 +222,39 @@ def test_argument_errors(plans):
     assert lib.cr_partial_grads(p, 16, 16, 16) == cr.CR_E_INVAL and "workspace" in cr.cr_last_error()
     assert lib.cr_encode_tree(p, 16) == cr.CR_E_INVAL
     assert lib.cr_plan_info(None, None) == cr.CR_E_INVAL
+
+
+def test_random_trees_against_the_oracle(plans):
+    """Seeded sweep over small trees and awkward sizes: allocation, decode rows and both work splits."""
+    rng = np.random.default_rng(2024)
+    for trial in range(25):
+        L = int(rng.integers(1, 4))
+        n = int(rng.integers(2, 6))
+        s = int(rng.integers(0, n))
+        N = cr_tree.num_workers(n, L)
+        m = int(N + rng.integers(0, 40 * N))
+        d = int(rng.choice([4, 12, 100, 257]))
+        p = plans(L, n, s, m, d)
+        info = cr.cr_plan_info(p)
+        Bo, _, gamma, cand = gc_code.design_code(n, s, L, cr.DEFAULT_SEED)
+        assert info.code_candidate == cand and info.gamma == pytest.approx(gamma, rel=1e-8)
+        B = cr.cr_plan_get_B(p)
+        np.testing.assert_allclose(B, Bo, atol=1e-11)
+        own, _ = cr_tree.cr_allocate(L, n, s, m, Bo)
+        node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+        expect = cr_tree.slabs_of(own)
+        assert [e[:3] for e in expect] == list(zip(node.tolist(), rb.tolist(), re_.tolist())), (L, n, s, m)
+        np.testing.assert_allclose(coef, [e[3] for e in expect], rtol=1e-10, atol=1e-13)
+        flags = (rng.random(n) < 0.3).astype(np.uint8)
+        if flags.sum() <= s:
+            a = cr.cr_plan_decode_row(p, flags)
+            T = cr_tree.padded_straggler_set(flags, s)
+            assert all(a[j] == 0 for j in T) and np.max(np.abs(a @ B - 1)) <= 1e-9
+        kind, value = (cr.CR_SPLIT_EQUAL_RANGES, int(rng.integers(1, 300))) if trial % 2 else (cr.CR_SPLIT_ROW_CELLS, int(rng.integers(1, 200)))
+        cr.cr_plan_set_split(p, kind, value)
+        slab, pb, pe, team = cr.cr_plan_get_pieces(p)
+        assert (pe - pb).sum() == info.row_visits and np.all(pe > pb)
+        cover = np.zeros(len(node), dtype=np.int64)
+        np.add.at(cover, slab, pe - pb)
+        assert np.array_equal(cover, re_ - rb)               # every slab is tiled exactly
+        assert np.all(pb >= rb[slab]) and np.all(pe <= re_[slab])
