@@ -355,3 +355,32 @@ def test_repeat_runs_are_bit_identical():
     b = hip.gradient(w_dev, mask).copy()
     assert np.array_equal(a, b)                          # fixed reduction order, no floating-point atomics
     hip.close()
+
+
+def test_random_small_problems():
+    """Seeded sweep over trees, widths, dtypes, models and work splits (each picks its own kernel variant)."""
+    rng = np.random.default_rng(77)
+    widths = [4, 20, 100, 260, 1000, 1032, 2052, 3000, 5001, 12_288]
+    for trial in range(24):
+        L = int(rng.integers(1, 4))
+        n = int(rng.integers(2, 6))
+        s = int(rng.integers(0, n))
+        N = wl.num_workers(n, L)
+        d = int(widths[trial % len(widths)])
+        m = int(N + rng.integers(1, max(2, 600_000 // d)))
+        model = cr.CR_LOGISTIC if trial % 3 == 0 else cr.CR_LINEAR
+        x_dtype = cr.CR_BF16 if trial % 4 == 1 else cr.CR_F32
+        base = "cfg3" if model == cr.CR_LOGISTIC else "cfg2"
+        cfg = wl.config(base, L=L, n=n, s=s, m=m, d=d, model=model, x_dtype=x_dtype, w0_std=None if model == cr.CR_LOGISTIC else 1.0,
+                        seed=1000 + trial)
+        data = wl.make_dataset(cfg)
+        split = [None, (cr.CR_SPLIT_EQUAL_RANGES, int(rng.integers(1, 2000))), (cr.CR_SPLIT_ROW_CELLS, int(rng.integers(1, 300)))][trial % 3]
+        print(f"trial {trial}: L={L} n={n} s={s} m={m} d={d} model={model} x_dtype={x_dtype} split={split}", flush=True)
+        hip = HipPath(L, n, s, data["X"], data["y"], model, x_dtype, teams=split)
+        orc = OraclePath(L, n, s, data["X"], data["y"], model)
+        mask = np.zeros(N, dtype=np.uint8)
+        for g in range(N // n):
+            k = int(rng.integers(0, s + 1))
+            mask[g * n + rng.choice(n, size=k, replace=False)] = 1
+        _check_iteration(hip, orc, data["w0"], mask, TOL[x_dtype])
+        hip.close()
