@@ -77,7 +77,7 @@ def test_allocation_sizes(L, n, s, m):
             assert k == cr_tree.set_size(W)
 
 
-def test_survey_sizes_of_benchmark_trees():
+def test_sizes_of_benchmark_trees():
     expect = {(2, 3, 1, 1200): (27, 3840), (2, 4, 1, 100_000): (36, 333_332), (3, 4, 1, 252_000): (148, 1_512_000),
               (2, 8, 2, 88): (248, 648), (3, 6, 2, 2_064_000): (780, 38_036_556)}
     for (L, n, s, m), (S, visits) in expect.items():
