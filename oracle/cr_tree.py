@@ -17,7 +17,7 @@ A *weighted set* is an ordered list of segments (row_begin, row_end, coef):
 the data points X[row_begin:row_end], each carrying the scalar `coef`
 (the paper's "b D" notation).  Coefficients may be floats or Fractions.
 
-Readings where the paper is silent (each is also listed in the design notes):
+Readings where the paper is silent:
   * k = n partitions per CompAlloc call, cut by position at floor(kappa*|W|/n);
   * a child's parts are concatenated in ascending partition index;
   * a node keeps the FIRST `own` positions of its sub-tree set, where

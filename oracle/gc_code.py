@@ -7,7 +7,7 @@ supported on the n-s survivors, with a_f B = (1,...,1).  The decoding matrix A
 stacks the F = C(n,s) rows.
 
 The paper cites the gradient-coding construction without restating it, so this
-module states one as mathematics (every reading is listed in the design notes):
+module states one as mathematics:
 
 * support of row i is the cyclic window {i, i+1, ..., i+s} mod n (the printed
   matrix of the (3,2) example has this support);
