@@ -85,7 +85,7 @@ typedef struct cr_plan_info {
  *   seed         seeds the counter-based search for a well-conditioned code (ignored when B is given)
  *   B_or_null    host, n*n doubles row-major: use this encoding matrix (s+1 non-zeros in every row and column); or NULL
  *   out          receives the plan; destroy with cr_plan_destroy
- * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, m<N, C(n,s) > 2^20, N > 2^24, a singular/unsupported B. */
+ * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, d>2^28, m<N, m>2^40, C(n,s) > 2^20, N > 2^24, an unsupported B. */
 int cr_plan(int L, int n, int s, int64_t m, int64_t d, cr_plan_t **out);
 int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype, uint64_t seed,
                const double *B_or_null, cr_plan_t **out);
@@ -134,7 +134,8 @@ int cr_bind_workspace(cr_plan_t *plan, void *dev_ptr, size_t bytes, void *hip_st
 /* ---- the hot path ------------------------------------------------------------------------------------------------
  * cr_partial_grads (CR.Execute step 1): for every slab p,  G[p] = X[b:e]^T (phi(X[b:e] w) - y[b:e]),  phi = identity or sigmoid.
  *   X_dev  m x d row-major, contiguous, fp32 or bf16 per the plan, 16-byte aligned;  y_dev m floats;  w_dev d floats.
- *   Every holder of a row reads it itself (the redundancy is the method); X is read once per holder.
+ *   Every holder of a row reads it itself (the redundancy is the method); X is read once per holder as long as a row fits the
+ *   registers of one team (d <= 24576 when d is a multiple of 4 (fp32) / 8 (bf16), else d <= 6144); wider rows take two passes.
  * cr_load_partial_grads: use caller-supplied slab gradients G_dev[S][d] (fp32, 16-byte aligned) in place of stage 1;
  *   the buffer is read in place by cr_encode_tree and must stay valid until then.
  * cr_encode_tree (CR.Execute steps 2-5): mask is HOST memory, N bytes, non-zero = straggler.  For every non-straggler node,

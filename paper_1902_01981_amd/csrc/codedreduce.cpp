@@ -78,7 +78,7 @@ struct cr_plan_s {
     int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr, *d_slab_pieces = nullptr;
     char *d_program = nullptr;                     // per-call encode program + root decode terms
     size_t program_bytes = 0;
-    float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr;
+    float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr, *d_residuals = nullptr;   // residuals: wide-row path only
     const float *G_src = nullptr;                  // slabs the encode reads: d_G or the caller's buffer
     char *h_staging = nullptr;                     // pinned, kStagingSlots * program_bytes
     hipEvent_t staging_done[kStagingSlots] = {};
@@ -129,20 +129,20 @@ constexpr int kL2Domains = 8;
 int ensure_split(cr_plan_t *p)
 {
     if (!p->split.pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
-    if (!p->variant) return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels");
+    const int teams_per_block = p->variant ? p->variant->teams_per_block() : 1;     // wide rows: one workgroup per piece
     int kind = p->split_kind;
     int64_t value = p->split_value;
     if (kind < 0 && p->s == 0) {
         // no redundancy (every row has one holder): nothing to share, so one contiguous range per resident workgroup streams best
         int dev = 0, cus = 0, per_cu = 0;
         int slots = 2 * 256;                                // MI355X: 256 CUs, two resident workgroups each; refined if a device is present
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        if (p->variant && hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn, p->variant->block(), 0) == hipSuccess && cus > 0 && per_cu > 0)
             slots = cus * per_cu;
         else
             (void)hipGetLastError();                        // no device: keep the default and clear the error
         kind = CR_SPLIT_EQUAL_RANGES;
-        value = static_cast<int64_t>(slots) * p->variant->teams_per_block();
+        value = static_cast<int64_t>(slots) * teams_per_block;
     }
     if (kind < 0) {
         // default: row cells of about 2 MB of X, between 96 and 512 rows, a multiple of 32.  Long enough that the d-float partial
@@ -156,7 +156,12 @@ int ensure_split(cr_plan_t *p)
     }
     if (kind == CR_SPLIT_ROW_CELLS) {
         if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        cr::split_row_cells(p->slabs, value, kL2Domains, p->variant->teams_per_block(), p->split);
+        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, p->split);
+        if (!p->variant) {                                  // the wide-row kernels index pieces directly: no empty teams
+            cr::Split compact;
+            cr::split_row_cells(p->slabs, value, 1, 1, compact);
+            p->split = compact;
+        }
     } else {
         const int teams = static_cast<int>(std::min<int64_t>(value, std::max<int64_t>(1, p->row_visits)));
         cr::split_equal_ranges(p->slabs, teams, p->split);
@@ -189,6 +194,7 @@ void compute_layout(cr_plan_t *p, size_t *total)
     if (p->model != CR_AGGREGATE_ONLY) {
         w = align_up(w + P * row, 256);
         w = align_up(w + S * row, 256);
+        if (!p->variant) w = align_up(w + static_cast<size_t>(p->row_visits) * sizeof(float), 256);
     }
     w = align_up(w + N * row, 256);
     *total = w;
@@ -286,8 +292,8 @@ int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype
         }
         if (p->slabs.size() > (size_t(1) << 30)) { delete p; return fail(CR_E_INVAL, "too many slabs"); }
         if (model != CR_AGGREGATE_ONLY) {
-            p->variant = cr::select_stage1(x_dtype, d);
-            if (!p->variant) { delete p; return fail(CR_E_INVAL, "d is outside the range of the single-pass partial-gradient kernels (d <= 24576 when d is a multiple of 4 (fp32) or 8 (bf16), else d <= 6144)"); }
+            p->variant = cr::select_stage1(x_dtype, d);     // nullptr: rows too wide for one team's registers, two-pass path
+            if (d > (int64_t(1) << 28)) { delete p; return fail(CR_E_INVAL, "d exceeds 2^28"); }
         }
     } catch (const std::bad_alloc &) {
         delete p;
@@ -444,14 +450,19 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     if (p->model != CR_AGGREGATE_ONLY) {
         p->d_partial = reinterpret_cast<float *>(p->ws + w);               w = align_up(w + P * row, 256);
         p->d_G = reinterpret_cast<float *>(p->ws + w);                     w = align_up(w + S * row, 256);
+        if (!p->variant) { p->d_residuals = reinterpret_cast<float *>(p->ws + w); w = align_up(w + static_cast<size_t>(p->row_visits) * sizeof(float), 256); }
     }
     p->d_M = reinterpret_cast<float *>(p->ws + w);                         w = align_up(w + N * row, 256);
     p->G_src = p->d_G;
 
     if (P > 0) {
         std::vector<cr::DevPiece> hp(P);
-        for (size_t i = 0; i < P; ++i)
-            hp[i] = {p->split.pieces[i].row_begin, static_cast<int32_t>(p->split.pieces[i].row_end - p->split.pieces[i].row_begin), p->split.pieces[i].slab};
+        int64_t visit = 0;
+        for (size_t i = 0; i < P; ++i) {
+            const int64_t rows = p->split.pieces[i].row_end - p->split.pieces[i].row_begin;
+            hp[i] = {p->split.pieces[i].row_begin, visit, static_cast<int32_t>(rows), p->split.pieces[i].slab};
+            visit += rows;
+        }
         CR_HIP(hipMemcpy(p->d_pieces, hp.data(), P * sizeof(cr::DevPiece), hipMemcpyHostToDevice));
         CR_HIP(hipMemcpy(p->d_team_piece_begin, p->split.team_piece_begin.data(), (p->split.teams + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
         CR_HIP(hipMemcpy(p->d_slab_piece_begin, p->split.slab_piece_begin.data(), (S + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -478,8 +489,14 @@ int cr_partial_grads(cr_plan_t *p, const void *X, const float *y, const float *w
         // what the method must move: every holder reads its rows and targets once, each slab gradient is written once
         const int64_t bytes = p->row_visits * p->d * elem_size(p) + p->row_visits * 4 + S * p->d * 4 + p->d * 4;
         LaunchTimer t(p, CR_K_PARTIAL_GRADS, bytes);
-        CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->split.teams, p->d_partial, p->d,
+        if (p->variant) {
+            CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->split.teams, p->d_partial, p->d,
+                                            p->model == CR_LOGISTIC ? 1 : 0, p->stream));
+        } else {
+            CR_HIP(cr::launch_residuals(p->x_dtype, X, y, w, p->d_pieces, static_cast<int>(P), p->d_residuals, p->d,
                                         p->model == CR_LOGISTIC ? 1 : 0, p->stream));
+            CR_HIP(cr::launch_xt_residuals(p->x_dtype, X, p->d_pieces, static_cast<int>(P), p->d_residuals, p->d_partial, p->d, p->stream));
+        }
         t.done();
     }
     {

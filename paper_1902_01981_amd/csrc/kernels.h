@@ -8,6 +8,7 @@ namespace cr {
 
 struct DevPiece {            // one stage-1 work item: rows [row_begin, row_begin + nrows) of X, partial row = index of the piece
     int64_t row_begin;
+    int64_t visit_begin;     // index of the piece's first row among all row visits, piece-major (wide-row path: where its residuals live)
     int32_t nrows;
     int32_t slab;
 };
@@ -48,6 +49,13 @@ const Stage1Variant *select_stage1(int x_dtype, int64_t d);
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
                                 hipStream_t stream);
+// Wide rows (a row does not fit the registers of one team): two passes.  launch_residuals writes phi(x.w) - y for every row visit,
+// launch_xt_residuals forms X^T r per piece and block of 256*kWideChunks*vec columns.  X is read twice on this path.
+constexpr int kWideChunks = 8;
+hipError_t launch_residuals(int x_dtype, const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces,
+                            float *residuals, int64_t d, int logistic, hipStream_t stream);
+hipError_t launch_xt_residuals(int x_dtype, const void *X, const DevPiece *pieces, int num_pieces, const float *residuals, float *partial,
+                               int64_t d, hipStream_t stream);
 hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G, int64_t d,
                                 hipStream_t stream);
 hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream);

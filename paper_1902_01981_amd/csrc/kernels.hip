@@ -172,6 +172,90 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
     }
 }
 
+// ---- stage 1 for wide rows -----------------------------------------------------------------------------------------
+// When a row is too long for one team's registers the single pass is split in two: first the residuals r = phi(x.w) - y of every
+// row visit (one workgroup per piece, the row streamed in chunks), then G_piece = X^T r per piece and column block.
+template <int XD, int VEC>
+__global__ void __launch_bounds__(256)
+residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
+                 const DevPiece *__restrict__ pieces, float *__restrict__ residuals, int64_t d, int nq, int logistic)
+{
+    using C = Chunk<XD, VEC>;
+    using raw_t = typename C::raw_t;
+    constexpr int U = 8;                                 // chunks in flight per thread
+    const DevPiece pc = pieces[blockIdx.x];
+    __shared__ float red[2][4];
+    int buf = 0;
+    for (int r = 0; r < pc.nrows; ++r) {
+        const raw_t *rowp = C::row(X, (pc.row_begin + r) * d);
+        float s = 0.f;
+        for (int q0 = threadIdx.x; q0 < nq; q0 += 256 * U) {
+            raw_t xr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) xr[u] = rowp[min(q0 + u * 256, nq - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = q0 + u * 256;
+                if (q < nq) {
+                    float xv[VEC];
+                    C::widen(xr[u], xv);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], w[static_cast<int64_t>(q) * VEC + v], s);
+                }
+            }
+        }
+        s = wave_sum(s);
+        if ((threadIdx.x & 63) == 0) red[buf][threadIdx.x / 64] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const float z = red[buf][0] + red[buf][1] + red[buf][2] + red[buf][3];
+            const float ph = logistic ? 1.f / (1.f + __expf(-z)) : z;
+            residuals[pc.visit_begin + r] = ph - y[pc.row_begin + r];
+        }
+        buf ^= 1;
+    }
+}
+
+template <int XD, int VEC>
+__global__ void __launch_bounds__(256)
+xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pieces, const float *__restrict__ residuals,
+                    float *__restrict__ partial, int64_t d, int nq)
+{
+    using C = Chunk<XD, VEC>;
+    using raw_t = typename C::raw_t;
+    constexpr int K = kWideChunks;
+    const DevPiece pc = pieces[blockIdx.y];
+    const int qbase = blockIdx.x * (256 * K) + threadIdx.x;
+    int qi[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) qi[k] = min(qbase + k * 256, nq - 1);
+    float acc[K][VEC];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
+    for (int r = 0; r < pc.nrows; ++r) {
+        const raw_t *rowp = C::row(X, (pc.row_begin + r) * d);
+        const float res = residuals[pc.visit_begin + r];
+        raw_t xr[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) xr[k] = rowp[qi[k]];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            float xv[VEC];
+            C::widen(xr[k], xv);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[k][v] = fmaf(res, xv[v], acc[k][v]);
+        }
+    }
+    float *out = partial + static_cast<int64_t>(blockIdx.y) * d;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int q = qbase + k * 256;
+        if (q < nq) store_row<VEC>(out + static_cast<int64_t>(q) * VEC, acc[k]);
+    }
+}
+
 // ---- piece reduction ------------------------------------------------------------------------------------------------
 template <int VEC>
 __global__ void __launch_bounds__(256)
@@ -435,6 +519,44 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
     return hipLaunchKernel(v.fn, grid, block, args, 0, stream);
+}
+
+namespace {
+template <int XD, int VEC>
+hipError_t launch_wide(const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces, float *residuals,
+                       float *partial, int64_t d, int logistic, hipStream_t stream)
+{
+    const int nq = static_cast<int>(d / VEC);
+    if (partial == nullptr)
+        residuals_kernel<XD, VEC><<<num_pieces, 256, 0, stream>>>(X, y, w, pieces, residuals, d, nq, logistic);
+    else
+        xt_residuals_kernel<XD, VEC><<<dim3((nq + 256 * kWideChunks - 1) / (256 * kWideChunks), num_pieces), 256, 0, stream>>>(
+            X, pieces, residuals, partial, d, nq);
+    return hipGetLastError();
+}
+
+hipError_t dispatch_wide(int x_dtype, const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces,
+                         float *residuals, float *partial, int64_t d, int logistic, hipStream_t stream)
+{
+    if (x_dtype == 0) {
+        if (d % 4 == 0) return launch_wide<0, 4>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+        return launch_wide<0, 1>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+    }
+    if (d % 8 == 0) return launch_wide<1, 8>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+    return launch_wide<1, 1>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+}
+}  // namespace
+
+hipError_t launch_residuals(int x_dtype, const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces,
+                            float *residuals, int64_t d, int logistic, hipStream_t stream)
+{
+    return dispatch_wide(x_dtype, X, y, w, pieces, num_pieces, residuals, nullptr, d, logistic, stream);
+}
+
+hipError_t launch_xt_residuals(int x_dtype, const void *X, const DevPiece *pieces, int num_pieces, const float *residuals, float *partial,
+                               int64_t d, hipStream_t stream)
+{
+    return dispatch_wide(x_dtype, X, nullptr, nullptr, pieces, num_pieces, const_cast<float *>(residuals), partial, d, 0, stream);
 }
 
 hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G,

@@ -104,6 +104,9 @@ CASES = [
     ("m-equals-N", 2, 3, 1, 12, 64, cr.CR_LINEAR, cr.CR_F32, None),               # one row per worker
     ("gc-master-worker", 1, 10, 4, 10_000, 512, cr.CR_LINEAR, cr.CR_F32, None),   # one layer, 10 workers, 4 stragglers (fractional repetition)
     ("uncoded-master-worker", 1, 10, 0, 10_000, 512, cr.CR_LINEAR, cr.CR_F32, None),
+    ("wide-rows-fp32", 2, 3, 1, 400, 30_000, cr.CR_LINEAR, cr.CR_F32, None),      # beyond one team's registers: two-pass stage 1
+    ("wide-rows-bf16", 2, 4, 1, 500, 50_008, cr.CR_LOGISTIC, cr.CR_BF16, None),
+    ("wide-rows-odd", 1, 3, 1, 200, 25_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_EQUAL_RANGES, 40)),
     ("cr-12x2-s3", 2, 12, 3, 31_200, 320, cr.CR_LOGISTIC, cr.CR_F32, None),       # the paper's (12,2) tree, 156 workers, 3 stragglers per group
 ]
 

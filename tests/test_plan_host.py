@@ -215,8 +215,9 @@ def test_argument_errors(plans):
         assert ei.value.status == cr.CR_E_INVAL, args
     with pytest.raises(cr.CodedReduceError):
         plans(2, 3, 1, 100, 4, B=np.eye(3))             # one partition per worker cannot survive a straggler
-    with pytest.raises(cr.CodedReduceError):
-        plans(2, 3, 1, 100, 30_000)                     # beyond the single-pass kernels
+    p_wide = plans(2, 3, 1, 100, 30_000)                # rows too wide for the single-pass kernel: still planned (two-pass path)
+    cr.cr_plan_set_split(p_wide, cr.CR_SPLIT_ROW_CELLS, 16)
+    assert cr.cr_plan_info(p_wide).num_pieces == cr.cr_plan_info(p_wide).num_teams      # no empty teams on that path
     p = plans(2, 3, 1, 100, 4)
     lib = cr.load_library()
     assert lib.cr_partial_grads(p, 16, 16, 16) == cr.CR_E_INVAL and "workspace" in cr.cr_last_error()
