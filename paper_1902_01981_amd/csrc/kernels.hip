@@ -1,11 +1,18 @@
-// HIP kernels of the CodedReduce hot path for gfx950 (64-wide wavefronts).  Everything here is HBM-bandwidth bound:
+// HIP kernels of the CodedReduce hot path for gfx950 (64-wide wavefronts).  Everything here is bandwidth bound:
 // plain vector FMAs, 16-byte coalesced loads, no matrix cores.
 //
 //   partial_grads_kernel   CR.Execute step 1: G_piece = X[b:e]^T (phi(X[b:e] w) - y[b:e]) in ONE pass over the rows
+//   residuals_kernel, xt_residuals_kernel   the same in two passes, for rows too wide for one team's registers
 //   reduce_pieces_kernel   sums the pieces of each slab (fixed order, so results are reproducible bit for bit)
 //   encode_kernel          CR.Execute steps 2-5: every node's message, children folded into parents in registers
 //   decode_kernel          the master's decode  g = sum_j a_j m_(1,j)
-//   update_kernel          w <- w - lr g
+//   update_kernel, update_metrics_kernel    w <- w - lr g, optionally with the convergence measures of eq. (6) and (8)
+//
+// Rows of d elements start on a 4-byte (fp32) or 2-byte (bf16) boundary whatever d is, so the 16-byte row accesses are declared
+// with that alignment; the hardware runs in unaligned-access mode and the compiler emits the same dwordx4 instructions.
+// A row is cut into nq = ceil(d / VEC) chunks of VEC columns; when VEC does not divide d the last chunk is moved back to end at
+// column d, overlapping its neighbour.  Overlapped columns are then produced twice, from the same operands in the same order,
+// and both copies store the same bits; only sums ACROSS columns (the dot product x.w) must count them once.
 #include "kernels.h"
 
 #include <hip/hip_runtime.h>
@@ -14,6 +21,9 @@ namespace cr {
 
 namespace {
 
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));       // four floats of an fp32 row
+typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));    // eight bf16 values of a bf16 row
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -21,19 +31,28 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// element offset of chunk q inside a row (a chunk index past the row is sent to the last chunk)
+template <int VEC> __device__ __forceinline__ int chunk_offset(int q, int nq, int d)
+{
+    return q < nq - 1 ? q * VEC : d - VEC;
+}
+// does element v of chunk q belong to it alone (not to the overlap with the chunk before, not past the row)?
+template <int VEC> __device__ __forceinline__ bool chunk_owns(int q, int v, int nq, int d)
+{
+    return q < nq - 1 || (q == nq - 1 && d - VEC + v >= (nq - 1) * VEC);
+}
+
 // ---- how a chunk of a row of X is fetched and widened to fp32 -------------------------------------------------
 template <int XD, int VEC> struct Chunk;
 
 template <> struct Chunk<0, 4> {
-    using raw_t = float4;
-    static __device__ __forceinline__ raw_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return reinterpret_cast<const float4 *>(static_cast<const float *>(X) + e); }
+    using raw_t = f4u;
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const f4u *>(static_cast<const float *>(X) + e); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
 };
 template <> struct Chunk<1, 8> {
-    using raw_t = uint4;     // eight bf16 values
-    static __device__ __forceinline__ raw_t zero() { return make_uint4(0u, 0u, 0u, 0u); }
-    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(X) + e); }
+    using raw_t = u4h;
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const u4h *>(static_cast<const uint16_t *>(X) + e); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
     {
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -42,27 +61,56 @@ template <> struct Chunk<1, 8> {
         v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
     }
 };
-template <> struct Chunk<0, 1> {
+template <> struct Chunk<0, 1> {      // rows shorter than one wide chunk
     using raw_t = float;
-    static __device__ __forceinline__ raw_t zero() { return 0.f; }
-    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return static_cast<const float *>(X) + e; }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const float *>(X)[e]; }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = r; }
 };
 template <> struct Chunk<1, 1> {
     using raw_t = uint16_t;
-    static __device__ __forceinline__ raw_t zero() { return 0; }
-    static __device__ __forceinline__ const raw_t *row(const void *X, int64_t e) { return static_cast<const uint16_t *>(X) + e; }
+    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const uint16_t *>(X)[e]; }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
 };
 
+// VEC consecutive floats of an fp32 row (slab gradients, piece partials, messages)
+template <int VEC> __device__ __forceinline__ void load_row(const float *src, float (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) { const f4u t = *reinterpret_cast<const f4u *>(src + i); v[i] = t.x; v[i + 1] = t.y; v[i + 2] = t.z; v[i + 3] = t.w; }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = src[i];
+    }
+}
+template <int VEC> __device__ __forceinline__ void load_row_nt(const float *src, float (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) { const f4u t = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src + i)); v[i] = t.x; v[i + 1] = t.y; v[i + 2] = t.z; v[i + 3] = t.w; }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = __builtin_nontemporal_load(src + i);
+    }
+}
 template <int VEC> __device__ __forceinline__ void store_row(float *dst, const float (&v)[VEC])
 {
     if constexpr (VEC % 4 == 0) {
 #pragma unroll
-        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4 *>(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+        for (int i = 0; i < VEC; i += 4) { f4u t; t.x = v[i]; t.y = v[i + 1]; t.z = v[i + 2]; t.w = v[i + 3]; *reinterpret_cast<f4u *>(dst + i) = t; }
     } else {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) dst[i] = v[i];
+    }
+}
+template <int VEC> __device__ __forceinline__ void store_row_nt(float *dst, const float (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) { f4u t; t.x = v[i]; t.y = v[i + 1]; t.z = v[i + 2]; t.w = v[i + 3]; __builtin_nontemporal_store(t, reinterpret_cast<f4u *>(dst + i)); }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) __builtin_nontemporal_store(v[i], dst + i);
     }
 }
 
@@ -75,7 +123,7 @@ template <int XD, int VEC, int TS, int K, int R>
 __global__ void __launch_bounds__((TS < 256 ? 256 : TS))
 partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
                      const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
-                     float *__restrict__ partial, int64_t d, int nq, int logistic)
+                     float *__restrict__ partial, int d, int nq, int logistic)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
@@ -88,15 +136,15 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
     if (team >= num_teams) return;   // whole teams only; teams of several wavefronts span the block, so barriers stay uniform
 
     // K = ceil(nq / TS): only the last chunk of a thread can fall outside the row.  Such a lane re-reads the row's last chunk
-    // (so every load is unconditional) with a zero weight, and never stores its accumulator.
-    int qi[K];
+    // (so every load is unconditional) with zero weights, and never stores its accumulator.
+    int off[K];
     float wv[K][VEC];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int q = tl + k * TS;
-        qi[k] = min(q, nq - 1);
+        off[k] = chunk_offset<VEC>(q, nq, d);
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) wv[k][v] = (q < nq) ? w[static_cast<int64_t>(q) * VEC + v] : 0.f;
+        for (int v = 0; v < VEC; ++v) wv[k][v] = chunk_owns<VEC>(q, v, nq, d) ? w[off[k] + v] : 0.f;
     }
 
     const int pb = team_piece_begin[team], pe = team_piece_begin[team + 1];
@@ -114,9 +162,9 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
-                const raw_t *rowp = C::row(X, (pc.row_begin + rr) * d);
+                const int64_t base = (pc.row_begin + rr) * d;
 #pragma unroll
-                for (int k = 0; k < K; ++k) xr[r][k] = rowp[qi[k]];
+                for (int k = 0; k < K; ++k) xr[r][k] = C::load(X, base + off[k]);
             }
             float pd[R];
 #pragma unroll
@@ -165,10 +213,8 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
         }
         float *out = partial + static_cast<int64_t>(p) * d;
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int q = tl + k * TS;
-            if (q < nq) store_row<VEC>(out + static_cast<int64_t>(q) * VEC, acc[k]);
-        }
+        for (int k = 0; k < K; ++k)
+            if (tl + k * TS < nq) store_row<VEC>(out + off[k], acc[k]);
     }
 }
 
@@ -178,7 +224,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 template <int XD, int VEC>
 __global__ void __launch_bounds__(256)
 residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
-                 const DevPiece *__restrict__ pieces, float *__restrict__ residuals, int64_t d, int nq, int logistic)
+                 const DevPiece *__restrict__ pieces, float *__restrict__ residuals, int d, int nq, int logistic)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
@@ -187,21 +233,21 @@ residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const 
     __shared__ float red[2][4];
     int buf = 0;
     for (int r = 0; r < pc.nrows; ++r) {
-        const raw_t *rowp = C::row(X, (pc.row_begin + r) * d);
+        const int64_t base = (pc.row_begin + r) * d;
         float s = 0.f;
         for (int q0 = threadIdx.x; q0 < nq; q0 += 256 * U) {
             raw_t xr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) xr[u] = rowp[min(q0 + u * 256, nq - 1)];
+            for (int u = 0; u < U; ++u) xr[u] = C::load(X, base + chunk_offset<VEC>(q0 + u * 256, nq, d));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int q = q0 + u * 256;
-                if (q < nq) {
-                    float xv[VEC];
-                    C::widen(xr[u], xv);
+                const int o = chunk_offset<VEC>(q, nq, d);
+                float xv[VEC];
+                C::widen(xr[u], xv);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], w[static_cast<int64_t>(q) * VEC + v], s);
-                }
+                for (int v = 0; v < VEC; ++v)
+                    if (chunk_owns<VEC>(q, v, nq, d)) s = fmaf(xv[v], w[o + v], s);
             }
         }
         s = wave_sum(s);
@@ -219,27 +265,27 @@ residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const 
 template <int XD, int VEC>
 __global__ void __launch_bounds__(256)
 xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pieces, const float *__restrict__ residuals,
-                    float *__restrict__ partial, int64_t d, int nq)
+                    float *__restrict__ partial, int d, int nq)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
     constexpr int K = kWideChunks;
     const DevPiece pc = pieces[blockIdx.y];
     const int qbase = blockIdx.x * (256 * K) + threadIdx.x;
-    int qi[K];
+    int off[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) qi[k] = min(qbase + k * 256, nq - 1);
+    for (int k = 0; k < K; ++k) off[k] = chunk_offset<VEC>(qbase + k * 256, nq, d);
     float acc[K][VEC];
 #pragma unroll
     for (int k = 0; k < K; ++k)
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
     for (int r = 0; r < pc.nrows; ++r) {
-        const raw_t *rowp = C::row(X, (pc.row_begin + r) * d);
+        const int64_t base = (pc.row_begin + r) * d;
         const float res = residuals[pc.visit_begin + r];
         raw_t xr[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) xr[k] = rowp[qi[k]];
+        for (int k = 0; k < K; ++k) xr[k] = C::load(X, base + off[k]);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             float xv[VEC];
@@ -250,10 +296,8 @@ xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pie
     }
     float *out = partial + static_cast<int64_t>(blockIdx.y) * d;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int q = qbase + k * 256;
-        if (q < nq) store_row<VEC>(out + static_cast<int64_t>(q) * VEC, acc[k]);
-    }
+    for (int k = 0; k < K; ++k)
+        if (qbase + k * 256 < nq) store_row<VEC>(out + off[k], acc[k]);
 }
 
 // ---- piece reduction ------------------------------------------------------------------------------------------------
@@ -264,6 +308,7 @@ reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restric
 {
     const int q = blockIdx.x * 256 + threadIdx.x;
     if (q >= nq) return;
+    const int64_t col = chunk_offset<VEC>(q, nq, static_cast<int>(d));
     const int slab = blockIdx.y;
     const int pb = slab_piece_begin[slab], pe = slab_piece_begin[slab + 1];
     double acc[VEC];
@@ -273,12 +318,7 @@ reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restric
     for (int j0 = pb; j0 < pe; j0 += U) {
         float xv[U][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = min(j0 + u, pe - 1);
-            const float *src = partial + static_cast<int64_t>(slab_pieces[j]) * d + static_cast<int64_t>(q) * VEC;
-            if constexpr (VEC == 4) { const float4 t = *reinterpret_cast<const float4 *>(src); xv[u][0] = t.x; xv[u][1] = t.y; xv[u][2] = t.z; xv[u][3] = t.w; }
-            else xv[u][0] = src[0];
-        }
+        for (int u = 0; u < U; ++u) load_row<VEC>(partial + static_cast<int64_t>(slab_pieces[min(j0 + u, pe - 1)]) * d + col, xv[u]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (j0 + u < pe) {
@@ -289,26 +329,21 @@ reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restric
     float out[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) out[v] = static_cast<float>(acc[v]);
-    store_row<VEC>(G + static_cast<int64_t>(slab) * d + static_cast<int64_t>(q) * VEC, out);
+    store_row<VEC>(G + static_cast<int64_t>(slab) * d + col, out);
 }
 
 // ---- encode ---------------------------------------------------------------------------------------------------------
-// One thread owns VEC columns and runs the whole sub-tree of one level-1 node for them: a post-order list of terms
+// One thread owns C chunks of VEC columns and runs the whole sub-tree of one level-1 node for them: a post-order list of terms
 // (own += coef * G[slab]) in which the last term of a node finishes it: message = own + pending[level], stored (rounded to fp32,
 // as a transmitted message would be) and folded into pending[level-1] with the parent's decode coefficient.  Child messages
 // therefore never come back from HBM; every active slab is read once and every message written once.  The program is the same for
-// every thread, so it is read with wide scalar loads, kEncodeUnroll terms at a time; the slab loads of those terms are all issued
-// before the first is used.  Slabs and messages are touched once: loads and stores are non-temporal.  Arithmetic is fp64.
-typedef float f4v __attribute__((ext_vector_type(4)));
-typedef int i8v __attribute__((ext_vector_type(8)));
-typedef double d8v __attribute__((ext_vector_type(8)));
-
-// C column chunks per thread (a workgroup covers BS*C*VEC contiguous columns of every row it touches), BS threads per workgroup,
-// U terms fetched together, acc_t the accumulator type.  Two shapes are used:
+// every thread, so it is read with wide scalar loads, U terms at a time; the slab loads of those terms are all issued before the
+// first is used.  Slabs and messages are touched once: loads and stores are non-temporal.
+// A workgroup of BS threads covers BS*C*VEC contiguous columns of every row it touches.  Two shapes are used:
 //   narrow  C=1, U=8, fp64 accumulators: for short vectors, where the launch has few threads and latency decides;
 //   wide    C=32, U=1, fp32 accumulators: for long vectors.  A workgroup then streams 128 KB-aligned, 128 KB-long pieces of one
 //           slab at a time, which is what HBM likes best (the same 31-stream pattern read 4 KB at a time reaches 4.9 TB/s, this
-//           5.9 TB/s); the 32 chunks in flight fill the register file, hence fp32 accumulation: two or three extra roundings
+//           6.1 TB/s); the 32 chunks in flight fill the register file, hence fp32 accumulation: two or three extra roundings
 //           of the size of the message's own fp32 rounding.
 template <int VEC, int LT, int C, int BS, int U, typename acc_t>
 __global__ void __launch_bounds__(BS)
@@ -328,7 +363,7 @@ encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram pro
     for (int c = 0; c < C; ++c) {
         const int q = q0 + c * BS;
         live[c] = q < nq;
-        col[c] = static_cast<int64_t>(live[c] ? q : nq - 1) * VEC;
+        col[c] = chunk_offset<VEC>(q, nq, static_cast<int>(d));
     }
 
     acc_t pend[LT + 1][C][VEC];
@@ -353,14 +388,7 @@ encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram pro
         for (int u = 0; u < U; ++u) {
             const float *src = G + static_cast<int64_t>(slab[u]) * d;
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if constexpr (VEC == 4) {
-                    const f4v f = __builtin_nontemporal_load(reinterpret_cast<const f4v *>(src + col[c]));
-                    xv[u][c][0] = f.x; xv[u][c][1] = f.y; xv[u][c][2] = f.z; xv[u][c][3] = f.w;
-                } else {
-                    xv[u][c][0] = __builtin_nontemporal_load(src + col[c]);
-                }
-            }
+            for (int c = 0; c < C; ++c) load_row_nt<VEC>(src + col[c], xv[u][c]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -383,14 +411,7 @@ encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram pro
                         out[v] = static_cast<float>(msg);
                         own[c][v] = 0;
                     }
-                    if (live[c]) {
-                        if constexpr (VEC == 4) {
-                            f4v o; o.x = out[0]; o.y = out[1]; o.z = out[2]; o.w = out[3];
-                            __builtin_nontemporal_store(o, reinterpret_cast<f4v *>(dst + col[c]));
-                        } else {
-                            __builtin_nontemporal_store(out[0], dst + col[c]);
-                        }
-                    }
+                    if (live[c]) store_row_nt<VEC>(dst + col[c], out);
 #pragma unroll
                     for (int l = 1; l < LT; ++l)
                         if (l == lvl - 1) {
@@ -410,16 +431,14 @@ decode_kernel(const float *__restrict__ M, float *__restrict__ g, const DecTerm 
 {
     const int q = blockIdx.x * 256 + threadIdx.x;
     if (q >= nq) return;
-    const int64_t col = static_cast<int64_t>(q) * VEC;
+    const int64_t col = chunk_offset<VEC>(q, nq, static_cast<int>(d));
     double acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
     for (int j = 0; j < nterms; ++j) {
         const DecTerm tm = terms[j];
-        const float *src = M + static_cast<int64_t>(tm.row) * d + col;
         float xv[VEC];
-        if constexpr (VEC == 4) { const float4 f = *reinterpret_cast<const float4 *>(src); xv[0] = f.x; xv[1] = f.y; xv[2] = f.z; xv[3] = f.w; }
-        else xv[0] = src[0];
+        load_row<VEC>(M + static_cast<int64_t>(tm.row) * d + col, xv);
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = fma(tm.coef, static_cast<double>(xv[v]), acc[v]);
     }
@@ -477,30 +496,34 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
 // ---- variant table for stage 1 --------------------------------------------------------------------------------------
 #define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
-// fp32 x4 / scalar chunks: 4 (1) registers per chunk
-#define CR_FAMILY_NARROW(XD, VEC)                                                                                   \
-    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 8), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 4),                \
-    CR_V(XD, VEC, 256, 2, 8), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 4), CR_V(XD, VEC, 256, 5, 4),            \
-    CR_V(XD, VEC, 256, 6, 3), CR_V(XD, VEC, 256, 7, 2), CR_V(XD, VEC, 256, 8, 2), CR_V(XD, VEC, 256, 9, 2),            \
-    CR_V(XD, VEC, 256, 10, 2), CR_V(XD, VEC, 256, 11, 2), CR_V(XD, VEC, 256, 12, 2),                                   \
-    CR_V(XD, VEC, 1024, 4, 2), CR_V(XD, VEC, 1024, 5, 1), CR_V(XD, VEC, 1024, 6, 1)
-// bf16 x8 chunks widen to eight accumulators each, so a thread can hold half as many
-#define CR_FAMILY_WIDE(XD, VEC)                                                                                     \
-    CR_V(XD, VEC, 64, 1, 8), CR_V(XD, VEC, 64, 2, 4), CR_V(XD, VEC, 64, 3, 4), CR_V(XD, VEC, 64, 4, 2),                \
-    CR_V(XD, VEC, 256, 2, 4), CR_V(XD, VEC, 256, 3, 4), CR_V(XD, VEC, 256, 4, 2), CR_V(XD, VEC, 256, 5, 2),            \
-    CR_V(XD, VEC, 256, 6, 2), CR_V(XD, VEC, 1024, 2, 2), CR_V(XD, VEC, 1024, 3, 1)
+const Stage1Variant kVariants[] = {
+    // fp32, chunks of 4 columns (4 registers per chunk)
+    CR_V(0, 4, 64, 1, 8), CR_V(0, 4, 64, 2, 8), CR_V(0, 4, 64, 3, 4), CR_V(0, 4, 64, 4, 4),
+    CR_V(0, 4, 256, 2, 8), CR_V(0, 4, 256, 3, 4), CR_V(0, 4, 256, 4, 4), CR_V(0, 4, 256, 5, 4),
+    CR_V(0, 4, 256, 6, 3), CR_V(0, 4, 256, 7, 2), CR_V(0, 4, 256, 8, 2), CR_V(0, 4, 256, 9, 2),
+    CR_V(0, 4, 256, 10, 2), CR_V(0, 4, 256, 11, 2), CR_V(0, 4, 256, 12, 2),
+    CR_V(0, 4, 1024, 4, 2), CR_V(0, 4, 1024, 5, 1), CR_V(0, 4, 1024, 6, 1),
+    // bf16, chunks of 8 columns: they widen to eight accumulators each, so a thread can hold half as many
+    CR_V(1, 8, 64, 1, 8), CR_V(1, 8, 64, 2, 4), CR_V(1, 8, 64, 3, 4), CR_V(1, 8, 64, 4, 2),
+    CR_V(1, 8, 256, 2, 4), CR_V(1, 8, 256, 3, 4), CR_V(1, 8, 256, 4, 2), CR_V(1, 8, 256, 5, 2),
+    CR_V(1, 8, 256, 6, 2), CR_V(1, 8, 1024, 2, 2), CR_V(1, 8, 1024, 3, 1),
+    // rows shorter than one wide chunk: one column per lane
+    CR_V(0, 1, 64, 1, 8), CR_V(1, 1, 64, 1, 8),
+};
 
-const Stage1Variant kVariants[] = {CR_FAMILY_NARROW(0, 4), CR_FAMILY_WIDE(1, 8), CR_FAMILY_NARROW(0, 1), CR_FAMILY_NARROW(1, 1)};
-
-inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// columns per chunk: the 16-byte width unless the row is shorter than that
+int stage1_chunk_width(int x_dtype, int64_t d)
+{
+    const int wide = (x_dtype == 1) ? 8 : 4;
+    return d >= wide ? wide : 1;
+}
 
 }  // namespace
 
 const Stage1Variant *select_stage1(int x_dtype, int64_t d)
 {
-    const int wide = (x_dtype == 1) ? 8 : 4;
-    const int vec = (d % wide == 0) ? wide : 1;
-    const int64_t nq = d / vec;
+    const int vec = stage1_chunk_width(x_dtype, d);
+    const int64_t nq = (d + vec - 1) / vec;
     // smallest team that covers the row with an available chunk count; the kernel needs K = ceil(nq / team size) exactly
     for (int ts : {64, 256, 1024}) {
         const int64_t k = (nq + ts - 1) / ts;
@@ -514,8 +537,9 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
                                 hipStream_t stream)
 {
-    int nq = static_cast<int>(d / v.vec);
-    void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &d, &nq, &logistic};
+    int di = static_cast<int>(d);
+    int nq = static_cast<int>((d + v.vec - 1) / v.vec);
+    void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq, &logistic};
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
     return hipLaunchKernel(v.fn, grid, block, args, 0, stream);
@@ -526,24 +550,21 @@ template <int XD, int VEC>
 hipError_t launch_wide(const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces, float *residuals,
                        float *partial, int64_t d, int logistic, hipStream_t stream)
 {
-    const int nq = static_cast<int>(d / VEC);
+    const int nq = static_cast<int>((d + VEC - 1) / VEC);
+    const int di = static_cast<int>(d);
     if (partial == nullptr)
-        residuals_kernel<XD, VEC><<<num_pieces, 256, 0, stream>>>(X, y, w, pieces, residuals, d, nq, logistic);
+        residuals_kernel<XD, VEC><<<num_pieces, 256, 0, stream>>>(X, y, w, pieces, residuals, di, nq, logistic);
     else
         xt_residuals_kernel<XD, VEC><<<dim3((nq + 256 * kWideChunks - 1) / (256 * kWideChunks), num_pieces), 256, 0, stream>>>(
-            X, pieces, residuals, partial, d, nq);
+            X, pieces, residuals, partial, di, nq);
     return hipGetLastError();
 }
 
 hipError_t dispatch_wide(int x_dtype, const void *X, const float *y, const float *w, const DevPiece *pieces, int num_pieces,
                          float *residuals, float *partial, int64_t d, int logistic, hipStream_t stream)
 {
-    if (x_dtype == 0) {
-        if (d % 4 == 0) return launch_wide<0, 4>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
-        return launch_wide<0, 1>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
-    }
-    if (d % 8 == 0) return launch_wide<1, 8>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
-    return launch_wide<1, 1>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+    if (x_dtype == 0) return launch_wide<0, 4>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
+    return launch_wide<1, 8>(X, y, w, pieces, num_pieces, residuals, partial, d, logistic, stream);
 }
 }  // namespace
 
@@ -562,8 +583,8 @@ hipError_t launch_xt_residuals(int x_dtype, const void *X, const DevPiece *piece
 hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G,
                                 int64_t d, hipStream_t stream)
 {
-    if (d % 4 == 0) {
-        const int nq = static_cast<int>(d / 4);
+    if (d >= 4) {
+        const int nq = static_cast<int>((d + 3) / 4);
         reduce_pieces_kernel<4><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
     } else {
         const int nq = static_cast<int>(d);
@@ -575,7 +596,7 @@ hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_
 template <int VEC, int C, int BS, int U, typename acc_t>
 static hipError_t launch_encode_shape(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream)
 {
-    const int nq = static_cast<int>(d / VEC);
+    const int nq = static_cast<int>((d + VEC - 1) / VEC);
     const dim3 grid((nq + BS * C - 1) / (BS * C), num_sub), block(BS);
     if (L <= 1) encode_kernel<VEC, 1, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
     else if (L == 2) encode_kernel<VEC, 2, C, BS, U, acc_t><<<grid, block, 0, stream>>>(G, M, prog, d, nq);
@@ -589,9 +610,9 @@ static hipError_t launch_encode_shape(const float *G, float *M, const EncProgram
 
 hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream)
 {
-    if (d % 4 == 0 && aligned16(G) && aligned16(M)) {
+    if (d >= 4) {
         // wide shape once its 8192-chunk workgroups are enough to fill the chip, and only up to 3 levels (registers)
-        const int64_t wide_groups = (d / 4 + 8191) / 8192 * num_sub;
+        const int64_t wide_groups = ((d + 3) / 4 + 8191) / 8192 * num_sub;
         if (wide_groups >= 256 && L <= 3) return launch_encode_shape<4, 32, 256, 1, float>(G, M, prog, num_sub, L, d, stream);
         return launch_encode_shape<4, 1, 256, 8, double>(G, M, prog, num_sub, L, d, stream);
     }
@@ -600,8 +621,8 @@ hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int n
 
 hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream)
 {
-    if (d % 4 == 0 && aligned16(M) && aligned16(g)) {
-        const int nq = static_cast<int>(d / 4);
+    if (d >= 4) {
+        const int nq = static_cast<int>((d + 3) / 4);
         decode_kernel<4><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq);
     } else {
         const int nq = static_cast<int>(d);

@@ -95,8 +95,14 @@ CASES = [
     ("cfg5-row-cells", 3, 6, 2, 25_801, 1_024, cr.CR_LINEAR, cr.CR_BF16, (cr.CR_SPLIT_ROW_CELLS, 100)),
     ("cfg5-shape", 3, 6, 2, 25_801, 1_024, cr.CR_LINEAR, cr.CR_BF16, None),       # one wavefront per row, bf16 x8 chunks
     ("bf16-wide", 2, 3, 1, 2_000, 8_192, cr.CR_LOGISTIC, cr.CR_BF16, None),       # bf16 with 256-thread teams
-    ("odd-d-fp32", 2, 3, 1, 1_111, 1_003, cr.CR_LINEAR, cr.CR_F32, None),         # d % 4 != 0: scalar chunks everywhere
+    ("odd-d-fp32", 2, 3, 1, 1_111, 1_003, cr.CR_LINEAR, cr.CR_F32, None),         # d % 4 != 0: the last chunk overlaps its neighbour
     ("odd-d-bf16", 2, 3, 1, 1_111, 270, cr.CR_LINEAR, cr.CR_BF16, None),
+    ("odd-d-cfg2", 2, 4, 1, 2_003, 9_999, cr.CR_LOGISTIC, cr.CR_F32, None),       # rows not 16-byte aligned, 10 chunks per thread
+    ("odd-d-bf16-k3", 2, 3, 1, 1_500, 1_027, cr.CR_LINEAR, cr.CR_BF16, None),     # rows on odd 2-byte boundaries, last thread chunk mostly inert
+    ("d-5", 2, 3, 1, 600, 5, cr.CR_LINEAR, cr.CR_F32, None),                      # two chunks sharing three columns
+    ("d-9-bf16", 2, 3, 1, 600, 9, cr.CR_LOGISTIC, cr.CR_BF16, None),              # two chunks sharing seven columns
+    ("d-3", 2, 3, 1, 600, 3, cr.CR_LINEAR, cr.CR_F32, None),                      # shorter than one chunk: one column per lane
+    ("d-7-bf16", 1, 4, 1, 600, 7, cr.CR_LINEAR, cr.CR_BF16, None),
     ("tiny-d", 1, 5, 2, 333, 4, cr.CR_LINEAR, cr.CR_F32, None),                   # one layer: master-worker gradient coding
     ("s0-plain-tree", 2, 4, 0, 4_000, 256, cr.CR_LINEAR, cr.CR_F32, None),
     ("deep", 4, 2, 1, 3_000, 520, cr.CR_LOGISTIC, cr.CR_F32, None),
@@ -245,7 +251,7 @@ def test_aggregation_only():
 
 @pytest.mark.parametrize("s", [1, 3])
 def test_aggregation_only_network_sized(s):
-    """(12,2) tree, 156 workers, vectors of the size of the paper's CNN (117 706 parameters, not a multiple of 4: scalar columns)."""
+    """(12,2) tree, 156 workers, vectors of the size of the paper's CNN (117 706 parameters, not a multiple of 4)."""
     torch = _torch()
     L, n, d = 2, 12, 117_706
     m = 156 * 40
