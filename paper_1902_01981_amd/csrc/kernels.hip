@@ -24,11 +24,32 @@ namespace {
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));       // four floats of an fp32 row
 typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));    // eight bf16 values of a bf16 row
 
-__device__ __forceinline__ float wave_sum(float v)
+// v + (v of the lane that the cross-lane pattern CTRL pairs this lane with, inside its row of 16 lanes)
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over the 64 lanes, delivered to every lane.  The four steps inside a row of 16 lanes are adds that read the partner lane
+// directly (quad swaps, then the mirrored half-row and row: for a sum a mirror does what an exchange does).  The two steps across
+// rows either go through the LDS crossbar (2 adds + 2 LDS operations), or pass lane 15 / lane 31 on to the following rows so
+// that lane 63 ends with the total, which is then read into a scalar register (5 vector operations, no LDS round trip).
+// Kernels limited by vector-ALU issue (bf16 rows: a widening operation per element on top of the two multiply-adds) take the
+// first form, kernels limited by cache bandwidth and latency (fp32 rows) the second.
+template <bool VIA_LDS> __device__ __forceinline__ float wave_sum(float v)
+{
+    v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);     // row_half_mirror
+    v = dpp_add<0x140>(v);     // row_mirror
+    if constexpr (VIA_LDS) {
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        return v;
+    } else {
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1 and 3
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2 and 3
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    }
 }
 
 // element offset of chunk q inside a row (a chunk index past the row is sent to the last chunk)
@@ -43,16 +64,21 @@ template <int VEC> __device__ __forceinline__ bool chunk_owns(int q, int v, int 
 }
 
 // ---- how a chunk of a row of X is fetched and widened to fp32 -------------------------------------------------
+// load(row, e): the chunk at element e of the row that starts at `row` (a wave-uniform pointer; e differs per lane)
 template <int XD, int VEC> struct Chunk;
+template <int XD> __device__ __forceinline__ const void *row_ptr(const void *X, int64_t row, int d)
+{
+    return static_cast<const char *>(X) + row * d * (XD == 1 ? 2 : 4);
+}
 
 template <> struct Chunk<0, 4> {
     using raw_t = f4u;
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const f4u *>(static_cast<const float *>(X) + e); }
+    static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const f4u *>(static_cast<const char *>(row) + e * 4u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
 };
 template <> struct Chunk<1, 8> {
     using raw_t = u4h;
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return *reinterpret_cast<const u4h *>(static_cast<const uint16_t *>(X) + e); }
+    static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const u4h *>(static_cast<const char *>(row) + e * 2u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
     {
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -63,12 +89,12 @@ template <> struct Chunk<1, 8> {
 };
 template <> struct Chunk<0, 1> {      // rows shorter than one wide chunk
     using raw_t = float;
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const float *>(X)[e]; }
+    static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const float *>(static_cast<const char *>(row) + e * 4u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = r; }
 };
 template <> struct Chunk<1, 1> {
     using raw_t = uint16_t;
-    static __device__ __forceinline__ raw_t load(const void *X, int64_t e) { return static_cast<const uint16_t *>(X)[e]; }
+    static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const uint16_t *>(static_cast<const char *>(row) + e * 2u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
 };
 
@@ -137,7 +163,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 
     // K = ceil(nq / TS): only the last chunk of a thread can fall outside the row.  Such a lane re-reads the row's last chunk
     // (so every load is unconditional) with zero weights, and never stores its accumulator.
-    int off[K];
+    unsigned off[K];
     float wv[K][VEC];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -162,9 +188,9 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
-                const int64_t base = (pc.row_begin + rr) * d;
+                const void *row = row_ptr<XD>(X, pc.row_begin + rr, d);
 #pragma unroll
-                for (int k = 0; k < K; ++k) xr[r][k] = C::load(X, base + off[k]);
+                for (int k = 0; k < K; ++k) xr[r][k] = C::load(row, off[k]);
             }
             float pd[R];
 #pragma unroll
@@ -177,7 +203,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], wv[k][v], s);
                 }
-                pd[r] = wave_sum(s);
+                pd[r] = wave_sum<XD == 1>(s);
             }
             if constexpr (WAVES > 1) {
                 const int wave = tl / 64;
@@ -233,12 +259,12 @@ residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const 
     __shared__ float red[2][4];
     int buf = 0;
     for (int r = 0; r < pc.nrows; ++r) {
-        const int64_t base = (pc.row_begin + r) * d;
+        const void *row = row_ptr<XD>(X, pc.row_begin + r, d);
         float s = 0.f;
         for (int q0 = threadIdx.x; q0 < nq; q0 += 256 * U) {
             raw_t xr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) xr[u] = C::load(X, base + chunk_offset<VEC>(q0 + u * 256, nq, d));
+            for (int u = 0; u < U; ++u) xr[u] = C::load(row, chunk_offset<VEC>(q0 + u * 256, nq, d));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int q = q0 + u * 256;
@@ -250,7 +276,7 @@ residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const 
                     if (chunk_owns<VEC>(q, v, nq, d)) s = fmaf(xv[v], w[o + v], s);
             }
         }
-        s = wave_sum(s);
+        s = wave_sum<true>(s);
         if ((threadIdx.x & 63) == 0) red[buf][threadIdx.x / 64] = s;
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -272,7 +298,7 @@ xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pie
     constexpr int K = kWideChunks;
     const DevPiece pc = pieces[blockIdx.y];
     const int qbase = blockIdx.x * (256 * K) + threadIdx.x;
-    int off[K];
+    unsigned off[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) off[k] = chunk_offset<VEC>(qbase + k * 256, nq, d);
     float acc[K][VEC];
@@ -281,11 +307,11 @@ xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pie
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
     for (int r = 0; r < pc.nrows; ++r) {
-        const int64_t base = (pc.row_begin + r) * d;
+        const void *row = row_ptr<XD>(X, pc.row_begin + r, d);
         const float res = residuals[pc.visit_begin + r];
         raw_t xr[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) xr[k] = C::load(X, base + off[k]);
+        for (int k = 0; k < K; ++k) xr[k] = C::load(row, off[k]);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             float xv[VEC];
@@ -301,35 +327,55 @@ xt_residuals_kernel(const void *__restrict__ X, const DevPiece *__restrict__ pie
 }
 
 // ---- piece reduction ------------------------------------------------------------------------------------------------
+// G[slab] = sum of the slab's pieces.  A workgroup covers 64 chunks of columns of one slab; its four wavefronts each add up every
+// fourth piece (eight loads in flight per lane), then the four partial sums are combined through LDS.  The order of the
+// additions is fixed by the piece list alone, so the result is the same bits on every run; the sums are carried in fp64.
 template <int VEC>
 __global__ void __launch_bounds__(256)
 reduce_pieces_kernel(const float *__restrict__ partial, const int32_t *__restrict__ slab_piece_begin, const int32_t *__restrict__ slab_pieces,
                      float *__restrict__ G, int64_t d, int nq)
 {
-    const int q = blockIdx.x * 256 + threadIdx.x;
-    if (q >= nq) return;
+    constexpr int WAVES = 4;
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = min(static_cast<int>(blockIdx.x) * 64 + lane, nq - 1);     // lanes past the row repeat its last chunk and do not store
     const int64_t col = chunk_offset<VEC>(q, nq, static_cast<int>(d));
     const int slab = blockIdx.y;
     const int pb = slab_piece_begin[slab], pe = slab_piece_begin[slab + 1];
     double acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
-    constexpr int U = 8;                                 // pieces fetched together; the additions keep their fixed order
-    for (int j0 = pb; j0 < pe; j0 += U) {
+    for (int j0 = pb + wave; j0 < pe; j0 += WAVES * U) {
         float xv[U][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) load_row<VEC>(partial + static_cast<int64_t>(slab_pieces[min(j0 + u, pe - 1)]) * d + col, xv[u]);
+        for (int u = 0; u < U; ++u) {
+            const int j = min(j0 + u * WAVES, pe - 1);
+            load_row<VEC>(partial + static_cast<int64_t>(slab_pieces[j]) * d + col, xv[u]);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (j0 + u < pe) {
+            if (j0 + u * WAVES < pe) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc[v] += static_cast<double>(xv[u][v]);
             }
     }
-    float out[VEC];
+    __shared__ double part[WAVES - 1][VEC][64];
+    if (wave > 0) {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) out[v] = static_cast<float>(acc[v]);
-    store_row<VEC>(G + static_cast<int64_t>(slab) * d + col, out);
+        for (int v = 0; v < VEC; ++v) part[wave - 1][v][lane] = acc[v];
+    }
+    __syncthreads();
+    if (wave == 0 && static_cast<int>(blockIdx.x) * 64 + lane < nq) {
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            double t = acc[v];
+#pragma unroll
+            for (int k = 0; k < WAVES - 1; ++k) t += part[k][v][lane];
+            out[v] = static_cast<float>(t);
+        }
+        store_row<VEC>(G + static_cast<int64_t>(slab) * d + col, out);
+    }
 }
 
 // ---- encode ---------------------------------------------------------------------------------------------------------
@@ -585,10 +631,10 @@ hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_
 {
     if (d >= 4) {
         const int nq = static_cast<int>((d + 3) / 4);
-        reduce_pieces_kernel<4><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
+        reduce_pieces_kernel<4><<<dim3((nq + 63) / 64, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
     } else {
         const int nq = static_cast<int>(d);
-        reduce_pieces_kernel<1><<<dim3((nq + 255) / 256, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
+        reduce_pieces_kernel<1><<<dim3((nq + 63) / 64, num_slabs), 256, 0, stream>>>(partial, slab_piece_begin, slab_pieces, G, d, nq);
     }
     return hipGetLastError();
 }
