@@ -94,6 +94,7 @@ def main() -> int:
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle work for the CPU baseline (0 = skip)")
     ap.add_argument("--teams", type=int, default=0, help="stage-1 split: this many equal contiguous ranges")
     ap.add_argument("--cell-rows", type=int, default=0, help="stage-1 split: row cells of this many rows")
+    ap.add_argument("--shared-rows", type=int, default=0, help="stage-1 split: cells of at most this many rows shared through LDS")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain 1 GiB elementwise copy kernel a few times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -127,6 +128,8 @@ def main() -> int:
         cr.cr_plan_set_split(plan, cr.CR_SPLIT_EQUAL_RANGES, args.teams)
     elif args.cell_rows and not aggregate:
         cr.cr_plan_set_split(plan, cr.CR_SPLIT_ROW_CELLS, args.cell_rows)
+    elif args.shared_rows and not aggregate:
+        cr.cr_plan_set_split(plan, cr.CR_SPLIT_SHARED_CELLS, args.shared_rows)
 
     # ---- inputs, generated on the host from the seed and moved to HBM before any timing
     data = None

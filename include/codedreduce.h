@@ -105,9 +105,12 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *                          cut again at slab boundaries.
  *   CR_SPLIT_ROW_CELLS     value = rows per cell: every slab is cut on one global grid of that many rows, one piece per team, teams
  *                          ordered by cell so that the holders of the same rows run at the same time.
- * Default (when this is never called): row cells of about 2 MB of X (96 to 512 rows); with s = 0 (no row is held
- * twice) equal ranges, one per resident workgroup.  CR_E_STATE once a workspace is bound. */
-enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1 };
+ *   CR_SPLIT_SHARED_CELLS  value = most rows per cell: the grid is laid between slab boundaries, so every holder of a cell holds
+ *                          all of it; two holders share a workgroup, which fetches each row once into LDS for both (each still
+ *                          does all of its own arithmetic).  fp32 rows of 257 to 3072 16-byte chunks only, else CR_E_INVAL.
+ * Default (when this is never called): shared cells where that kernel exists, else row cells, of about 2 MB of X (96 to 512
+ * rows); with s = 0 (no row is held twice) equal ranges, one per resident workgroup.  CR_E_STATE once a workspace is bound. */
+enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1, CR_SPLIT_SHARED_CELLS = 2 };
 int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
 /* pieces in execution order: piece i is rows [row_begin[i], row_end[i]) of slab[i], run by team[i]; num_pieces entries each, any may be NULL */
 int cr_plan_get_pieces(const cr_plan_t *plan, int32_t *slab, int64_t *row_begin, int64_t *row_end, int32_t *team);

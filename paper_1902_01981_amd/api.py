@@ -19,7 +19,7 @@ CR_OK, CR_E_INVAL, CR_E_UNDECODABLE, CR_E_STATE, CR_E_HIP, CR_E_NOMEM = 0, -1, -
 CR_LINEAR, CR_LOGISTIC, CR_AGGREGATE_ONLY = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
 CR_K_PARTIAL_GRADS, CR_K_REDUCE_PIECES, CR_K_ENCODE, CR_K_DECODE, CR_K_UPDATE, CR_K_COUNT = 0, 1, 2, 3, 4, 5
-CR_SPLIT_EQUAL_RANGES, CR_SPLIT_ROW_CELLS = 0, 1
+CR_SPLIT_EQUAL_RANGES, CR_SPLIT_ROW_CELLS, CR_SPLIT_SHARED_CELLS = 0, 1, 2
 DEFAULT_SEED = 190201981
 
 EXPORTS = [

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <queue>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -64,7 +65,8 @@ struct cr_plan_s {
     mutable std::unordered_map<uint64_t, std::vector<double>> row_cache;   // padded straggler bitmask -> decode row
 
     // stage-1 split
-    const cr::Stage1Variant *variant = nullptr;
+    const cr::Stage1Variant *variant = nullptr;        // the stage-1 kernel in use (nullptr: two-pass path for very wide rows)
+    const cr::Stage1Variant *variant_regs = nullptr, *variant_staged = nullptr;   // what exists for (x_dtype, d)
     int split_kind = -1;                            // -1: choose from the device when the workspace is sized
     int64_t split_value = 0;
     cr::Split split;
@@ -129,9 +131,9 @@ constexpr int kL2Domains = 8;
 int ensure_split(cr_plan_t *p)
 {
     if (!p->split.pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
-    const int teams_per_block = p->variant ? p->variant->teams_per_block() : 1;     // wide rows: one workgroup per piece
     int kind = p->split_kind;
     int64_t value = p->split_value;
+    p->variant = p->variant_regs;
     if (kind < 0 && p->s == 0) {
         // no redundancy (every row has one holder): nothing to share, so one contiguous range per resident workgroup streams best
         int dev = 0, cus = 0, per_cu = 0;
@@ -142,7 +144,50 @@ int ensure_split(cr_plan_t *p)
         else
             (void)hipGetLastError();                        // no device: keep the default and clear the error
         kind = CR_SPLIT_EQUAL_RANGES;
-        value = static_cast<int64_t>(slots) * teams_per_block;
+        value = static_cast<int64_t>(slots) * (p->variant ? p->variant->teams_per_block() : 1);
+    }
+    // small problems (under 128 rows per compute unit and workgroup) do not repay the staged kernel's start-up: row cells below
+    if (kind < 0 && p->variant_staged && p->row_visits / p->variant_staged->teams_per_block() >= 256 * 128) {
+        // Rows staged through LDS: a workgroup occupies a compute unit alone and costs its rows plus a start-up of about 8 rows
+        // (pipeline fill, weights, the partial row it writes and the reduction reads back).  Workgroups are dealt to the 8 dies
+        // round-robin and each die gives the next one to its first free unit, so the time of a launch is the longest queue of that
+        // list schedule.  Take the cell height, 64 to 1024 rows, whose schedule ends first (measured: the ranking of the heights
+        // by this estimate is the ranking by run time on configurations 2 and 3); ties go to the taller cell.
+        kind = CR_SPLIT_SHARED_CELLS;
+        const int tpb = p->variant_staged->teams_per_block();
+        int dev = 0, cus = 0;
+        if (!(hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kL2Domains)) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        const int per_die = cus / kL2Domains;
+        value = 256;
+        if (p->row_visits / tpb / 64 <= (int64_t(1) << 17)) {       // beyond that the last round no longer matters
+            double best = -1.0;
+            cr::Split trial;
+            for (int64_t c = 64; c <= 1024; c += 32) {
+                cr::split_row_cells(p->slabs, c, kL2Domains, tpb, true, trial);
+                std::vector<std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>>> die(kL2Domains);
+                for (auto &q : die)
+                    for (int u = 0; u < per_die; ++u) q.push(0);
+                int64_t end = 0;
+                for (int g = 0; g * tpb < trial.teams; ++g) {
+                    int64_t rows = 0;
+                    for (int t = g * tpb; t < std::min(trial.teams, (g + 1) * tpb) && rows == 0; ++t)
+                        if (trial.team_piece_begin[t + 1] > trial.team_piece_begin[t]) {
+                            const cr::Piece &pc = trial.pieces[trial.team_piece_begin[t]];
+                            rows = pc.row_end - pc.row_begin;
+                        }
+                    if (rows == 0) continue;                         // a workgroup without work leaves at once
+                    auto &q = die[g % kL2Domains];
+                    const int64_t done = q.top() + rows + 8;
+                    q.pop();
+                    q.push(done);
+                    end = std::max(end, done);
+                }
+                if (best < 0.0 || static_cast<double>(end) <= best) { best = static_cast<double>(end); value = c; }
+            }
+        }
     }
     if (kind < 0) {
         // default: row cells of about 2 MB of X, between 96 and 512 rows, a multiple of 32.  Long enough that the d-float partial
@@ -154,13 +199,34 @@ int ensure_split(cr_plan_t *p)
         // small problems: shorter cells, so that there are a few thousand pieces to spread over the chip
         value = std::min<int64_t>(value, std::max<int64_t>(16, (p->row_visits / 2048 + 15) / 16 * 16));
     }
-    if (kind == CR_SPLIT_ROW_CELLS) {
-        if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, p->split);
+    if (kind == CR_SPLIT_SHARED_CELLS) {
+        if (!p->variant_staged) return fail(CR_E_INVAL, "no kernel stages rows of this width and type through LDS");
+        p->variant = p->variant_staged;
+    }
+    const int teams_per_block = p->variant ? p->variant->teams_per_block() : 1;     // wide rows: one workgroup per piece
+    if (kind == CR_SPLIT_ROW_CELLS || kind == CR_SPLIT_SHARED_CELLS) {
+        if (p->row_visits / value + 2 * static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
+        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, kind == CR_SPLIT_SHARED_CELLS, p->split);
         if (!p->variant) {                                  // the wide-row kernels index pieces directly: no empty teams
             cr::Split compact;
-            cr::split_row_cells(p->slabs, value, 1, 1, compact);
+            cr::split_row_cells(p->slabs, value, 1, 1, false, compact);
             p->split = compact;
+        }
+        if (kind == CR_SPLIT_SHARED_CELLS) {
+            // what the staged kernel relies on: at most one piece per team, and the same rows for every team of a workgroup
+            for (int g = 0; g * teams_per_block < p->split.teams; ++g) {
+                const cr::Piece *first = nullptr;
+                for (int t = g * teams_per_block; t < std::min(p->split.teams, (g + 1) * teams_per_block); ++t) {
+                    const int32_t pb = p->split.team_piece_begin[t], pe = p->split.team_piece_begin[t + 1];
+                    if (pe == pb) continue;
+                    const cr::Piece &pc = p->split.pieces[pb];
+                    if (pe - pb > 1 || (first && (first->row_begin != pc.row_begin || first->row_end != pc.row_end))) {
+                        p->split = cr::Split();
+                        return fail(CR_E_STATE, "shared cells: the teams of a workgroup do not hold the same rows");
+                    }
+                    if (!first) first = &pc;
+                }
+            }
         }
     } else {
         const int teams = static_cast<int>(std::min<int64_t>(value, std::max<int64_t>(1, p->row_visits)));
@@ -292,7 +358,11 @@ int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype
         }
         if (p->slabs.size() > (size_t(1) << 30)) { delete p; return fail(CR_E_INVAL, "too many slabs"); }
         if (model != CR_AGGREGATE_ONLY) {
-            p->variant = cr::select_stage1(x_dtype, d);     // nullptr: rows too wide for one team's registers, two-pass path
+            p->variant_regs = cr::select_stage1(x_dtype, d);          // nullptr: rows too wide for one team's registers, two-pass path
+            int64_t max_holders = 1;                                  // a leaf's rows sit in s+1 workers of every level above it
+            for (int l = 0; l < L && max_holders < 64; ++l) max_holders *= s + 1;
+            p->variant_staged = s > 0 ? cr::select_stage1_staged(x_dtype, d, max_holders) : nullptr;   // nullptr: no such kernel for this width
+            p->variant = p->variant_regs;
             if (d > (int64_t(1) << 28)) { delete p; return fail(CR_E_INVAL, "d exceeds 2^28"); }
         }
     } catch (const std::bad_alloc &) {
@@ -380,7 +450,7 @@ int cr_plan_decode_row(const cr_plan_t *p, const uint8_t *flags, double *a)
 int cr_plan_set_split(cr_plan_t *p, int kind, int64_t value)
 {
     if (!p) return fail(CR_E_INVAL, "NULL plan");
-    if (kind != CR_SPLIT_EQUAL_RANGES && kind != CR_SPLIT_ROW_CELLS) return fail(CR_E_INVAL, "unknown split kind");
+    if (kind != CR_SPLIT_EQUAL_RANGES && kind != CR_SPLIT_ROW_CELLS && kind != CR_SPLIT_SHARED_CELLS) return fail(CR_E_INVAL, "unknown split kind");
     if (value < 1) return fail(CR_E_INVAL, "split value must be >= 1");
     if (kind == CR_SPLIT_EQUAL_RANGES && value > (int64_t(1) << 24)) return fail(CR_E_INVAL, "too many teams");
     if (p->bound) return fail(CR_E_STATE, "the work split cannot change once a workspace is bound");
@@ -434,6 +504,13 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     compute_layout(p, &need);
     if (bytes < need) return fail(CR_E_INVAL, "workspace too small");
     if (p->bound) CR_HIP(hipStreamSynchronize(p->stream));
+    if (p->variant) {
+        int dev = 0, lds = 0;
+        CR_HIP(hipGetDevice(&dev));
+        CR_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+        if (p->variant->lds_bytes() > static_cast<size_t>(lds)) return fail(CR_E_INVAL, "the stage-1 kernel needs more LDS per workgroup than this device has");
+        CR_HIP(cr::prepare_stage1(*p->variant));
+    }
     p->stream = static_cast<hipStream_t>(hip_stream);
     p->ws = static_cast<char *>(dev_ptr);
     p->ws_bytes = bytes;

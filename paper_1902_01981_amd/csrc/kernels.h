@@ -35,16 +35,23 @@ struct DecTerm {             // g += coef * M[row]
 constexpr int kEncodeUnroll = 8;   // encode sub-programs are padded to a multiple of this many terms
 constexpr int kMaxLevels = 8;
 
-// Stage-1 kernel variant chosen for (x_dtype, d): team size, chunks per thread, rows in flight.
+// Stage-1 kernel variant chosen for (x_dtype, d): team size, chunks per thread, rows per step, teams per workgroup.
+// A `staged` variant fetches each row once per workgroup into LDS, from where all its teams (holders of the same rows) read it.
 struct Stage1Variant {
-    int xd, vec, team_size, k, rows;
+    int xd, vec, team_size, k, rows, tpb;
+    bool staged;
     const void *fn;
-    int block() const { return team_size < 256 ? 256 : team_size; }
-    int teams_per_block() const { return block() / team_size; }
+    int block() const { return team_size * tpb; }
+    int teams_per_block() const { return tpb; }
+    size_t lds_bytes() const;        // dynamic LDS the launch needs (0 for variants that keep rows in registers only)
 };
 
-// Returns nullptr if (x_dtype, d) is outside what the single-pass kernels cover.
+// Returns nullptr if (x_dtype, d) is outside what the single-pass register kernels cover.
 const Stage1Variant *select_stage1(int x_dtype, int64_t d);
+// The LDS-staged kernel for rows held by up to max_holders workers each, or nullptr if there is none for this type and width.
+const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_holders);
+// Once per variant and device before the first launch (raises the kernel's dynamic LDS limit where needed).
+hipError_t prepare_stage1(const Stage1Variant &v);
 
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,

@@ -2,6 +2,7 @@
 // plain vector FMAs, 16-byte coalesced loads, no matrix cores.
 //
 //   partial_grads_kernel   CR.Execute step 1: G_piece = X[b:e]^T (phi(X[b:e] w) - y[b:e]) in ONE pass over the rows
+//   partial_grads_staged_kernel   the same, with the rows fetched once per workgroup into LDS for several holders of those rows
 //   residuals_kernel, xt_residuals_kernel   the same in two passes, for rows too wide for one team's registers
 //   reduce_pieces_kernel   sums the pieces of each slab (fixed order, so results are reproducible bit for bit)
 //   encode_kernel          CR.Execute steps 2-5: every node's message, children folded into parents in registers
@@ -23,6 +24,8 @@ namespace {
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));       // four floats of an fp32 row
 typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));    // eight bf16 values of a bf16 row
+typedef float f4a __attribute__((ext_vector_type(4)));                   // the same chunks parked in LDS, 16-byte aligned there
+typedef unsigned u4a __attribute__((ext_vector_type(4)));
 
 // v + (v of the lane that the cross-lane pattern CTRL pairs this lane with, inside its row of 16 lanes)
 template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
@@ -52,6 +55,10 @@ template <bool VIA_LDS> __device__ __forceinline__ float wave_sum(float v)
     }
 }
 
+// 1 / (1 + e^-z) from the hardware exponential and reciprocal (each good to about one unit in the last place); it saturates to
+// 0 and 1 for large |z| without special cases
+__device__ __forceinline__ float sigmoid(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
+
 // element offset of chunk q inside a row (a chunk index past the row is sent to the last chunk)
 template <int VEC> __device__ __forceinline__ int chunk_offset(int q, int nq, int d)
 {
@@ -73,11 +80,13 @@ template <int XD> __device__ __forceinline__ const void *row_ptr(const void *X, 
 
 template <> struct Chunk<0, 4> {
     using raw_t = f4u;
+    using lds_t = f4a;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const f4u *>(static_cast<const char *>(row) + e * 4u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
 };
 template <> struct Chunk<1, 8> {
     using raw_t = u4h;
+    using lds_t = u4a;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const u4h *>(static_cast<const char *>(row) + e * 2u); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
     {
@@ -170,7 +179,10 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
         const int q = tl + k * TS;
         off[k] = chunk_offset<VEC>(q, nq, d);
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) wv[k][v] = chunk_owns<VEC>(q, v, nq, d) ? w[off[k] + v] : 0.f;
+        for (int v = 0; v < VEC; ++v) {
+            const float t = w[off[k] + v];               // always inside the row; masked after the load
+            wv[k][v] = chunk_owns<VEC>(q, v, nq, d) ? t : 0.f;
+        }
     }
 
     const int pb = team_piece_begin[team], pe = team_piece_begin[team + 1];
@@ -226,7 +238,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
                 const int rr = r0 + r;
                 const float yy = y[pc.row_begin + min(rr, pc.nrows - 1)];
                 const float z = pd[r];
-                const float ph = logistic ? 1.f / (1.f + __expf(-z)) : z;
+                const float ph = logistic ? sigmoid(z) : z;
                 const float res = (rr < pc.nrows) ? ph - yy : 0.f;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
@@ -241,6 +253,163 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
         for (int k = 0; k < K; ++k)
             if (tl + k * TS < nq) store_row<VEC>(out + off[k], acc[k]);
+    }
+}
+
+// ---- stage 1 with rows staged through LDS -----------------------------------------------------------------------------
+// The holders of a cell run the same rows.  Here H of them share a workgroup: its H*TS threads fetch every row once, pass it
+// through registers into LDS, and each team then reads the row from LDS and does its own dot product, residual and rank-1 update
+// exactly as above.  The L2 therefore serves a row once per workgroup instead of once per holder.
+// Software pipeline, one barrier per step of R rows: while step s is computed from one LDS buffer, step s+1 moves from registers
+// into the other buffer and the global loads of steps s+2 and s+3 are in flight in two register sets.
+// All teams of the workgroup must hold the same rows (cells cut at slab boundaries) and at most one piece each.
+template <int XD, int VEC, int TS, int K, int R, int H>
+__global__ void __launch_bounds__(TS * H)
+partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
+                            const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
+                            float *__restrict__ partial, int d, int nq, int logistic)
+{
+    using C = Chunk<XD, VEC>;
+    using raw_t = typename C::raw_t;
+    using lds_t = typename C::lds_t;
+    constexpr int BT = TS * H, WAVES = TS / 64, LPT = (K + H - 1) / H, ROW = LPT * BT;   // ROW chunks of LDS per staged row
+    extern __shared__ __align__(16) unsigned char smem[];
+    lds_t *stage = reinterpret_cast<lds_t *>(smem);                                       // [2][R][ROW]
+    float *red = reinterpret_cast<float *>(smem + sizeof(lds_t) * 2 * R * ROW);           // [H][2][R][WAVES]
+    const int tl = threadIdx.x % TS;
+    const int tib = __builtin_amdgcn_readfirstlane(threadIdx.x / TS);
+    const int wave = tl / 64;
+
+    // the rows of this workgroup are those of its first team that has a piece
+    int my_piece = -1, ref_piece = -1;
+#pragma unroll
+    for (int t = 0; t < H; ++t) {
+        const int team = blockIdx.x * H + t;
+        if (team < num_teams) {
+            const int pb = team_piece_begin[team];
+            if (team_piece_begin[team + 1] > pb) {
+                if (ref_piece < 0) ref_piece = pb;
+                if (t == tib) my_piece = pb;
+            }
+        }
+    }
+    if (ref_piece < 0) return;                          // the whole workgroup leaves: no barrier has been reached yet
+    const DevPiece pc = pieces[ref_piece];
+    const bool active = my_piece >= 0;                  // a team without a piece only helps to fetch
+    const int nsteps = (pc.nrows + R - 1) / R;
+
+    // fetch role: thread g of the workgroup brings chunks g, g+BT, ... of every row
+    unsigned goff[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) goff[j] = chunk_offset<VEC>(threadIdx.x + j * BT, nq, d);
+    // compute role: as in the register-only kernel
+    float wv[K][VEC];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int q = tl + k * TS;
+        const int o = chunk_offset<VEC>(q, nq, d);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const float t = w[o + v];
+            wv[k][v] = chunk_owns<VEC>(q, v, nq, d) ? t : 0.f;
+        }
+    }
+    float acc[K][VEC];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
+
+    auto fetch = [&](raw_t (&P)[R][LPT], int step) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rr = min(step * R + r, pc.nrows - 1);
+            const void *row = row_ptr<XD>(X, pc.row_begin + rr, d);
+#pragma unroll
+            for (int j = 0; j < LPT; ++j) P[r][j] = C::load(row, goff[j]);
+        }
+    };
+    auto park = [&](const raw_t (&P)[R][LPT], int buf) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int j = 0; j < LPT; ++j) stage[(buf * R + r) * ROW + threadIdx.x + j * BT] = __builtin_bit_cast(lds_t, P[r][j]);
+    };
+    // one step: rows step*R .. step*R+R-1 are in LDS buffer `cur`; `next` holds the rows of step+1 (loaded or still in flight)
+    auto step_fn = [&](int step, raw_t (&next)[R][LPT], int cur) {
+        park(next, cur ^ 1);
+        fetch(next, step + 3);                          // unconditional: the load queue then has a known depth at every wait
+        float pd[R], yy[R];
+        lds_t xr[R][K];
+        if (active) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) yy[r] = y[pc.row_begin + min(step * R + r, pc.nrows - 1)];   // asked for early, used after the barrier
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int k = 0; k < K; ++k) xr[r][k] = stage[(cur * R + r) * ROW + tl + k * TS];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float xv[VEC];
+                    C::widen(__builtin_bit_cast(raw_t, xr[r][k]), xv);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], wv[k][v], s);
+                }
+                pd[r] = wave_sum<XD == 1>(s);
+            }
+            if constexpr (WAVES > 1) {
+                if ((tl & 63) == 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) red[((tib * 2 + cur) * R + r) * WAVES + wave] = pd[r];
+                }
+            }
+        }
+        __syncthreads();
+        if (active) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float z = pd[r];
+                if constexpr (WAVES > 1) {
+                    z = 0.f;
+#pragma unroll
+                    for (int i = 0; i < WAVES; ++i) z += red[((tib * 2 + cur) * R + r) * WAVES + i];
+                }
+                const int rr = step * R + r;
+                const float ph = logistic ? sigmoid(z) : z;
+                const float res = (rr < pc.nrows) ? ph - yy[r] : 0.f;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float xv[VEC];
+                    C::widen(__builtin_bit_cast(raw_t, xr[r][k]), xv);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[k][v] = fmaf(res, xv[v], acc[k][v]);
+                }
+            }
+        }
+    };
+
+    raw_t P0[R][LPT], P1[R][LPT];
+    fetch(P0, 0);
+    fetch(P1, 1);                                       // steps past the end re-read the last row; nothing is computed from them
+    park(P0, 0);
+    fetch(P0, 2);
+    __syncthreads();
+    int step = 0;
+    for (; step + 1 < nsteps; step += 2) {              // two steps per trip, so that register sets and LDS buffers are fixed at compile time
+        step_fn(step, P1, 0);
+        step_fn(step + 1, P0, 1);
+    }
+    if (step < nsteps) step_fn(step, P1, 0);
+    if (active) {
+        float *out = partial + static_cast<int64_t>(my_piece) * d;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int q = tl + k * TS;
+            if (q < nq) store_row<VEC>(out + chunk_offset<VEC>(q, nq, d), acc[k]);
+        }
     }
 }
 
@@ -281,7 +450,7 @@ residuals_kernel(const void *__restrict__ X, const float *__restrict__ y, const 
         __syncthreads();
         if (threadIdx.x == 0) {
             const float z = red[buf][0] + red[buf][1] + red[buf][2] + red[buf][3];
-            const float ph = logistic ? 1.f / (1.f + __expf(-z)) : z;
+            const float ph = logistic ? sigmoid(z) : z;
             residuals[pc.visit_begin + r] = ph - y[pc.row_begin + r];
         }
         buf ^= 1;
@@ -540,7 +709,8 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
 }
 
 // ---- variant table for stage 1 --------------------------------------------------------------------------------------
-#define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
+#define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, (TS < 256 ? 256 / TS : 1), false, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
+#define CR_S(XD, VEC, TS, K, R, H) {XD, VEC, TS, K, R, H, true, reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H>)}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 const Stage1Variant kVariants[] = {
     // fp32, chunks of 4 columns (4 registers per chunk)
@@ -555,6 +725,16 @@ const Stage1Variant kVariants[] = {
     CR_V(1, 8, 256, 6, 2), CR_V(1, 8, 1024, 2, 2), CR_V(1, 8, 1024, 3, 1),
     // rows shorter than one wide chunk: one column per lane
     CR_V(0, 1, 64, 1, 8), CR_V(1, 1, 64, 1, 8),
+    // fp32 rows staged through LDS.  Eight holders per workgroup, one wavefront each, for rows of up to 1024 chunks ...
+    CR_S(0, 4, 64, 5, 1, 8), CR_S(0, 4, 64, 6, 1, 8), CR_S(0, 4, 64, 7, 1, 8), CR_S(0, 4, 64, 8, 1, 8), CR_S(0, 4, 64, 9, 1, 8),
+    CR_S(0, 4, 64, 10, 1, 8), CR_S(0, 4, 64, 11, 1, 8), CR_S(0, 4, 64, 12, 1, 8), CR_S(0, 4, 64, 13, 1, 8), CR_S(0, 4, 64, 14, 1, 8),
+    CR_S(0, 4, 64, 15, 1, 8), CR_S(0, 4, 64, 16, 1, 8),
+    // ... four holders of four wavefronts (1024 threads, so at most 128 registers each) up to 1536 chunks ...
+    CR_S(0, 4, 256, 2, 2, 4), CR_S(0, 4, 256, 3, 2, 4), CR_S(0, 4, 256, 4, 2, 4), CR_S(0, 4, 256, 5, 1, 4), CR_S(0, 4, 256, 6, 1, 4),
+    // ... two holders up to 3072 chunks; R is limited by the two LDS buffers of R rows each
+    CR_S(0, 4, 256, 2, 4, 2), CR_S(0, 4, 256, 3, 2, 2), CR_S(0, 4, 256, 4, 2, 2), CR_S(0, 4, 256, 5, 2, 2), CR_S(0, 4, 256, 6, 2, 2),
+    CR_S(0, 4, 256, 7, 1, 2), CR_S(0, 4, 256, 8, 1, 2), CR_S(0, 4, 256, 9, 1, 2), CR_S(0, 4, 256, 10, 1, 2),
+    CR_S(0, 4, 256, 11, 1, 2), CR_S(0, 4, 256, 12, 1, 2),
 };
 
 // columns per chunk: the 16-byte width unless the row is shorter than that
@@ -566,6 +746,13 @@ int stage1_chunk_width(int x_dtype, int64_t d)
 
 }  // namespace
 
+size_t Stage1Variant::lds_bytes() const
+{
+    if (!staged) return 0;
+    const size_t row_chunks = static_cast<size_t>((k + tpb - 1) / tpb) * block();
+    return 16 * 2 * rows * row_chunks + sizeof(float) * tpb * 2 * rows * (team_size / 64);
+}
+
 const Stage1Variant *select_stage1(int x_dtype, int64_t d)
 {
     const int vec = stage1_chunk_width(x_dtype, d);
@@ -574,9 +761,27 @@ const Stage1Variant *select_stage1(int x_dtype, int64_t d)
     for (int ts : {64, 256, 1024}) {
         const int64_t k = (nq + ts - 1) / ts;
         for (const Stage1Variant &v : kVariants)
-            if (v.xd == x_dtype && v.vec == vec && v.team_size == ts && v.k == k) return &v;
+            if (!v.staged && v.xd == x_dtype && v.vec == vec && v.team_size == ts && v.k == k) return &v;
     }
     return nullptr;
+}
+
+const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_holders)
+{
+    const int vec = stage1_chunk_width(x_dtype, d);
+    const int64_t nq = (d + vec - 1) / vec;
+    // the table lists workgroups of 8, then 4, then 2 holders: the first that is not wider than the rows need (3 holders still
+    // fill a workgroup of 4 better than two of 2; 5 and more take 8)
+    const int widest = max_holders >= 5 ? 8 : max_holders >= 3 ? 4 : 2;
+    for (const Stage1Variant &v : kVariants)
+        if (v.staged && v.xd == x_dtype && v.vec == vec && v.k == (nq + v.team_size - 1) / v.team_size && v.tpb <= widest) return &v;
+    return nullptr;
+}
+
+hipError_t prepare_stage1(const Stage1Variant &v)
+{
+    if (v.lds_bytes() <= 48 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(v.lds_bytes()));
 }
 
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
@@ -588,7 +793,7 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
     void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq, &logistic};
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
-    return hipLaunchKernel(v.fn, grid, block, args, 0, stream);
+    return hipLaunchKernel(v.fn, grid, block, args, v.lds_bytes(), stream);
 }
 
 namespace {

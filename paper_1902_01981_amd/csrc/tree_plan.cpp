@@ -159,17 +159,39 @@ void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out)
     index_slab_pieces(slabs.size(), out);
 }
 
-void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out)
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, bool whole_cells, Split &out)
 {
     struct Unit { int64_t cell; int32_t slab; int64_t row_begin, row_end; };
     std::vector<Unit> units;
-    for (size_t q = 0; q < slabs.size(); ++q) {
-        int64_t b = slabs[q].row_begin;
-        while (b < slabs[q].row_end) {
-            const int64_t cell = b / cell_rows;
-            const int64_t e = std::min(slabs[q].row_end, (cell + 1) * cell_rows);
-            units.push_back({cell, static_cast<int32_t>(q), b, e});
-            b = e;
+    if (!whole_cells) {
+        for (size_t q = 0; q < slabs.size(); ++q) {
+            int64_t b = slabs[q].row_begin;
+            while (b < slabs[q].row_end) {
+                const int64_t cell = b / cell_rows;
+                const int64_t e = std::min(slabs[q].row_end, (cell + 1) * cell_rows);
+                units.push_back({cell, static_cast<int32_t>(q), b, e});
+                b = e;
+            }
+        }
+    } else {
+        // Cells that every holder holds whole: the row axis is first cut wherever any slab begins or ends (between two such cuts
+        // the set of holders does not change), then every stretch is cut into near-equal cells of at most cell_rows rows.
+        std::vector<int64_t> cuts;
+        cuts.reserve(2 * slabs.size());
+        for (const Slab &sl : slabs) { cuts.push_back(sl.row_begin); cuts.push_back(sl.row_end); }
+        std::sort(cuts.begin(), cuts.end());
+        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+        std::vector<int64_t> first_cell(cuts.size(), 0);     // index of the first cell of the stretch that starts at cuts[i]
+        for (size_t i = 0; i + 1 < cuts.size(); ++i) first_cell[i + 1] = first_cell[i] + (cuts[i + 1] - cuts[i] + cell_rows - 1) / cell_rows;
+        for (size_t q = 0; q < slabs.size(); ++q) {
+            size_t i = static_cast<size_t>(std::lower_bound(cuts.begin(), cuts.end(), slabs[q].row_begin) - cuts.begin());
+            for (; i + 1 < cuts.size() && cuts[i] < slabs[q].row_end; ++i) {
+                const int64_t len = cuts[i + 1] - cuts[i];
+                const int64_t parts = (len + cell_rows - 1) / cell_rows;
+                for (int64_t c = 0; c < parts; ++c)
+                    units.push_back({first_cell[i] + c, static_cast<int32_t>(q), cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * c / parts),
+                                     cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * (c + 1) / parts)});
+            }
         }
     }
     std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.cell < b.cell; });

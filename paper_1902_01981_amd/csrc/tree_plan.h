@@ -61,6 +61,8 @@ void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out);
 // that the holders of the same rows are launched together and stream the same addresses at the same time (all but the first of them
 // are then served by the L2 cache instead of HBM).  `lanes` = number of L2 domains workgroups are dealt to round-robin,
 // `teams_per_block` = teams in one workgroup: the holders of a cell go to workgroup ids congruent modulo `lanes`.
-void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out);
+// With `whole_cells` the grid is laid inside the stretches between slab boundaries instead (cells of at most `cell_rows` rows),
+// so that every holder of a cell holds all of it: the teams of one workgroup then work on identical row ranges.
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, bool whole_cells, Split &out);
 
 }  // namespace cr

@@ -114,6 +114,16 @@ CASES = [
     ("wide-rows-bf16", 2, 4, 1, 500, 50_008, cr.CR_LOGISTIC, cr.CR_BF16, None),
     ("wide-rows-odd", 1, 3, 1, 200, 25_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_EQUAL_RANGES, 40)),
     ("cr-12x2-s3", 2, 12, 3, 31_200, 320, cr.CR_LOGISTIC, cr.CR_F32, None),       # the paper's (12,2) tree, 156 workers, 3 stragglers per group
+    # rows staged through LDS and shared by the holders in one workgroup
+    ("staged-2-holders", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # 10 chunks per thread, odd and even step counts
+    ("staged-2-holders-odd-d", 2, 4, 1, 2_003, 9_999, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 64)),
+    ("staged-4-holders", 2, 4, 1, 5_003, 2_052, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 50)),       # four 256-thread teams, two rows per step
+    ("staged-4-holders-k6", 2, 3, 1, 2_000, 5_640, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 90)),
+    ("staged-8-holders", 3, 4, 1, 8_400, 4_096, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 33)),     # eight one-wavefront teams, 16 chunks per thread
+    ("staged-8-holders-1-row", 3, 3, 1, 2_500, 3_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 1)),  # cells of a single row
+    ("staged-3-holders", 1, 5, 2, 4_001, 3_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 100)),      # one idle team per workgroup of four
+    ("staged-k12", 2, 3, 1, 900, 12_288, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 1000)),            # the widest staged rows
+    ("staged-default", 2, 4, 1, 140_000, 1_100, cr.CR_LINEAR, cr.CR_F32, None),                               # large enough for the staged default
 ]
 
 
@@ -384,6 +394,8 @@ def test_random_small_problems():
                         seed=1000 + trial)
         data = wl.make_dataset(cfg)
         split = [None, (cr.CR_SPLIT_EQUAL_RANGES, int(rng.integers(1, 2000))), (cr.CR_SPLIT_ROW_CELLS, int(rng.integers(1, 300)))][trial % 3]
+        if s > 0 and x_dtype == cr.CR_F32 and 1024 < d <= 12_288 and trial % 2 == 0:
+            split = (cr.CR_SPLIT_SHARED_CELLS, int(rng.integers(1, 300)))
         print(f"trial {trial}: L={L} n={n} s={s} m={m} d={d} model={model} x_dtype={x_dtype} split={split}", flush=True)
         hip = HipPath(L, n, s, data["X"], data["y"], model, x_dtype, teams=split)
         orc = OraclePath(L, n, s, data["X"], data["y"], model)

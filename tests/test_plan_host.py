@@ -166,6 +166,54 @@ def test_row_cell_split(plans, cell_rows):
         cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, 0)
 
 
+@pytest.mark.parametrize("L,n,s,m,d,per_group", [(2, 4, 1, 10_007, 10_000, 2), (3, 4, 1, 25_201, 4_096, 8), (2, 4, 1, 5_003, 2_052, 4),
+                                                  (1, 5, 2, 4_001, 3_001, 4), (2, 3, 1, 1_111, 1_028, 4)])
+@pytest.mark.parametrize("cell_rows", [1, 7, 50, 10 ** 6])
+def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
+    """Cells laid between slab boundaries: every team of a workgroup (per_group teams) holds exactly the same rows."""
+    p = plans(L, n, s, m, d)
+    cr.cr_plan_set_split(p, cr.CR_SPLIT_SHARED_CELLS, cell_rows)
+    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    slab, pb, pe, team = cr.cr_plan_get_pieces(p)
+    info = cr.cr_plan_info(p)
+    assert info.num_pieces == len(slab) <= info.num_teams and np.all(np.diff(team) > 0)   # at most one piece per team
+    assert np.all(pe > pb) and np.all(pe - pb <= cell_rows) and (pe - pb).sum() == info.row_visits
+    for q in range(len(node)):                          # the pieces of a slab tile its row range
+        idx = np.nonzero(slab == q)[0]
+        idx = idx[np.argsort(pb[idx])]
+        assert pb[idx[0]] == rb[q] and pe[idx[-1]] == re_[q] and np.array_equal(pb[idx[1:]], pe[idx[:-1]])
+    group = team // per_group
+    cuts = np.unique(np.concatenate([rb, re_]))
+    ranges = {}
+    for g, b, e in zip(group, pb, pe):
+        assert ranges.setdefault(g, (b, e)) == (b, e), g            # one row range per workgroup
+        i = np.searchsorted(cuts, b, side="right")
+        assert cuts[i - 1] <= b and e <= cuts[i]                     # no slab begins or ends inside a cell
+    holders = {}
+    for g, b in zip(group, pb):
+        holders.setdefault(b, set()).add(g % 8)
+    assert all(len(v) == 1 for v in holders.values())                # all workgroups of a cell sit on one L2 domain
+    # a holder count of h needs ceil(h / per_group) workgroups
+    count = {}
+    for b in pb:
+        count[b] = count.get(b, 0) + 1
+    groups_per_cell = {}
+    for g, b in set(zip(group, pb)):
+        groups_per_cell[b] = groups_per_cell.get(b, 0) + 1
+    assert all(groups_per_cell[b] == -(-count[b] // per_group) for b in count)
+
+
+def test_shared_cells_need_a_staged_kernel(plans):
+    for args, kw in [((2, 3, 1, 1_000, 64), {}), ((2, 3, 1, 1_000, 4_096), dict(x_dtype=cr.CR_BF16)), ((2, 3, 0, 1_000, 4_096), {}),
+                     ((2, 3, 1, 100, 20_000), {})]:
+        p = plans(*args, **kw)
+        with pytest.raises(cr.CodedReduceError) as ei:
+            cr.cr_plan_set_split(p, cr.CR_SPLIT_SHARED_CELLS, 64)
+        assert ei.value.status == cr.CR_E_INVAL
+        cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, 64)           # the plan is still usable
+        assert cr.cr_plan_info(p).num_pieces > 0
+
+
 @pytest.mark.parametrize("L,n,s,m", [(2, 3, 1, 1200), (1, 12, 3, 5000), (3, 4, 1, 25_200), (2, 12, 5, 49_920)])
 def test_run_time_model_matches_the_oracle(plans, L, n, s, m):
     from oracle import latency
