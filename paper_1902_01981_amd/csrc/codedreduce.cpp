@@ -139,7 +139,7 @@ int ensure_split(cr_plan_t *p)
         int dev = 0, cus = 0, per_cu = 0;
         int slots = 2 * 256;                                // MI355X: 256 CUs, two resident workgroups each; refined if a device is present
         if (p->variant && hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn, p->variant->block(), 0) == hipSuccess && cus > 0 && per_cu > 0)
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, p->variant->fn[0], p->variant->block(), 0) == hipSuccess && cus > 0 && per_cu > 0)
             slots = cus * per_cu;
         else
             (void)hipGetLastError();                        // no device: keep the default and clear the error

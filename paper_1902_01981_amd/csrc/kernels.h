@@ -40,7 +40,7 @@ constexpr int kMaxLevels = 8;
 struct Stage1Variant {
     int xd, vec, team_size, k, rows, tpb;
     bool staged;
-    const void *fn;
+    const void *fn[2];               // phi = identity, phi = sigmoid
     int block() const { return team_size * tpb; }
     int teams_per_block() const { return tpb; }
     size_t lds_bytes() const;        // dynamic LDS the launch needs (0 for variants that keep rows in registers only)

@@ -154,11 +154,11 @@ template <int VEC> __device__ __forceinline__ void store_row_nt(float *dst, cons
 // works on, so a row is fetched once, used for the dot product x.w, kept in registers, and used again for the rank-1 update
 // acc += (phi(x.w) - y) x.  R rows are in flight per step.  The dot is reduced inside the wavefront and, for teams of several
 // wavefronts, through LDS (double buffered: one barrier per step).  Each piece ends with one d-float store of the accumulators.
-template <int XD, int VEC, int TS, int K, int R>
+template <int XD, int VEC, int TS, int K, int R, bool LOGISTIC>
 __global__ void __launch_bounds__((TS < 256 ? 256 : TS))
 partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
                      const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
-                     float *__restrict__ partial, int d, int nq, int logistic)
+                     float *__restrict__ partial, int d, int nq)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
@@ -238,7 +238,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
                 const int rr = r0 + r;
                 const float yy = y[pc.row_begin + min(rr, pc.nrows - 1)];
                 const float z = pd[r];
-                const float ph = logistic ? sigmoid(z) : z;
+                const float ph = LOGISTIC ? sigmoid(z) : z;
                 const float res = (rr < pc.nrows) ? ph - yy : 0.f;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
@@ -263,11 +263,11 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 // Software pipeline, one barrier per step of R rows: while step s is computed from one LDS buffer, step s+1 moves from registers
 // into the other buffer and the global loads of steps s+2 and s+3 are in flight in two register sets.
 // All teams of the workgroup must hold the same rows (cells cut at slab boundaries) and at most one piece each.
-template <int XD, int VEC, int TS, int K, int R, int H>
+template <int XD, int VEC, int TS, int K, int R, int H, bool LOGISTIC>
 __global__ void __launch_bounds__(TS * H)
 partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
                             const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
-                            float *__restrict__ partial, int d, int nq, int logistic)
+                            float *__restrict__ partial, int d, int nq)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
@@ -378,7 +378,7 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
                     for (int i = 0; i < WAVES; ++i) z += red[((tib * 2 + cur) * R + r) * WAVES + i];
                 }
                 const int rr = step * R + r;
-                const float ph = logistic ? sigmoid(z) : z;
+                const float ph = LOGISTIC ? sigmoid(z) : z;
                 const float res = (rr < pc.nrows) ? ph - yy[r] : 0.f;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
@@ -709,8 +709,16 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
 }
 
 // ---- variant table for stage 1 --------------------------------------------------------------------------------------
-#define CR_V(XD, VEC, TS, K, R) {XD, VEC, TS, K, R, (TS < 256 ? 256 / TS : 1), false, reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R>)}
-#define CR_S(XD, VEC, TS, K, R, H) {XD, VEC, TS, K, R, H, true, reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H>)}
+// each variant is built twice, for phi = identity and phi = sigmoid: every lane forms the residual of every row, and the kernels
+// bound by vector-ALU issue would pay for evaluating both forms and selecting one
+#define CR_V(XD, VEC, TS, K, R)                                                                         \
+    {XD, VEC, TS, K, R, (TS < 256 ? 256 / TS : 1), false,                                               \
+     {reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, false>),                  \
+      reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, true>)}}
+#define CR_S(XD, VEC, TS, K, R, H)                                                                      \
+    {XD, VEC, TS, K, R, H, true,                                                                        \
+     {reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, false>),        \
+      reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, true>)}}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 const Stage1Variant kVariants[] = {
     // fp32, chunks of 4 columns (4 registers per chunk)
@@ -781,7 +789,11 @@ const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_ho
 hipError_t prepare_stage1(const Stage1Variant &v)
 {
     if (v.lds_bytes() <= 48 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(v.lds_bytes()));
+    for (const void *fn : v.fn) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(v.lds_bytes()));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
@@ -790,10 +802,10 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
 {
     int di = static_cast<int>(d);
     int nq = static_cast<int>((d + v.vec - 1) / v.vec);
-    void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq, &logistic};
+    void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq};
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
-    return hipLaunchKernel(v.fn, grid, block, args, v.lds_bytes(), stream);
+    return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, v.lds_bytes(), stream);
 }
 
 namespace {
