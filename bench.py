@@ -231,7 +231,10 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {DESCRIPTIONS[args.workload]}", "L": L, "n": n, "s": s, "m": m, "d": d,
                    "workers": info.num_workers, "slabs": info.num_slabs, "row_visits": info.row_visits,
-                   "stage1_teams": info.num_teams, "stage1_pieces": info.num_pieces, "code_gamma": info.gamma},
+                   "stage1_teams": info.num_teams, "stage1_pieces": info.num_pieces, "code_gamma": info.gamma,
+                   "stage1_split": ["equal_ranges", "row_cells", "shared_cells"][info.split_kind] if info.split_kind >= 0 else None,
+                   "stage1_split_value": info.split_value, "stage1_team_size": info.stage1_team_size,
+                   "stage1_holders_per_workgroup": info.stage1_teams_per_group if info.stage1_staged else 1},
         "algorithmic_GBps_whole_step": total_bytes / (elapsed / args.steps) / 1e9,
         "hbm_frac_whole_step": total_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "roofline": roofline,

@@ -68,9 +68,14 @@ typedef struct cr_plan_info {
     int32_t code_candidate;  /* index of the winning candidate of the code search; -1 if B was supplied; -2 fractional repetition */
     int32_t num_teams;       /* stage-1 work split (0 until known, see cr_plan_set_split) */
     int32_t num_pieces;      /* stage-1 partial rows (0 until the split is known) */
+    int32_t split_kind;      /* enum cr_split of the split in force; -1 until it is known */
+    int32_t stage1_team_size;       /* threads that share one row in the stage-1 kernel in force; 0: two-pass path for very wide rows */
+    int32_t stage1_teams_per_group; /* teams (holders) per workgroup of that kernel */
+    int32_t stage1_staged;   /* 1 if that kernel fetches rows once per workgroup into LDS */
     int64_t m, d;
     int64_t row_visits;      /* sum over workers of allocated rows */
     int64_t min_rows, max_rows; /* smallest / largest per-worker load; both equal r_CR m up to integer cuts (Theorem 1) */
+    int64_t split_value;     /* teams (equal ranges) or rows per cell (row cells, shared cells); 0 until the split is known */
     double gamma;            /* max_f sum_i |a_fi| ||b_i||_2 / sqrt(n): rounding amplification of one decode */
     double r_cr;             /* computation load of Theorem 1 */
 } cr_plan_info_t;
@@ -106,10 +111,13 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *   CR_SPLIT_ROW_CELLS     value = rows per cell: every slab is cut on one global grid of that many rows, one piece per team, teams
  *                          ordered by cell so that the holders of the same rows run at the same time.
  *   CR_SPLIT_SHARED_CELLS  value = most rows per cell: the grid is laid between slab boundaries, so every holder of a cell holds
- *                          all of it; two holders share a workgroup, which fetches each row once into LDS for both (each still
- *                          does all of its own arithmetic).  fp32 rows of 257 to 3072 16-byte chunks only, else CR_E_INVAL.
- * Default (when this is never called): shared cells where that kernel exists, else row cells, of about 2 MB of X (96 to 512
- * rows); with s = 0 (no row is held twice) equal ranges, one per resident workgroup.  CR_E_STATE once a workspace is bound. */
+ *                          all of it; 2, 4 or 8 holders (by row width and by (s+1)^L, the most holders a row can have) share a
+ *                          workgroup, which fetches each row once into LDS for all of them; each still does all of its own
+ *                          arithmetic.  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.
+ * Default (when this is never called): with s = 0 (no row is held twice) equal ranges, one per resident workgroup; else shared
+ * cells where that kernel exists and the problem has at least 128 rows per compute unit and workgroup, with the cell height
+ * (64 to 1024 rows) whose list schedule over the chip's compute units ends first; else row cells of about 2 MB of X (96 to
+ * 512 rows, fewer for small problems).  CR_E_STATE once a workspace is bound. */
 enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1, CR_SPLIT_SHARED_CELLS = 2 };
 int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
 /* pieces in execution order: piece i is rows [row_begin[i], row_end[i]) of slab[i], run by team[i]; num_pieces entries each, any may be NULL */

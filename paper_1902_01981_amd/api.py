@@ -38,8 +38,9 @@ class CodedReduceError(RuntimeError):
 
 class cr_plan_info_t(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("L", "n", "s", "model", "x_dtype", "num_workers", "num_groups", "num_slabs",
-                                              "num_decode_rows", "code_candidate", "num_teams", "num_pieces")] + \
-               [(k, ctypes.c_int64) for k in ("m", "d", "row_visits", "min_rows", "max_rows")] + \
+                                              "num_decode_rows", "code_candidate", "num_teams", "num_pieces", "split_kind",
+                                              "stage1_team_size", "stage1_teams_per_group", "stage1_staged")] + \
+               [(k, ctypes.c_int64) for k in ("m", "d", "row_visits", "min_rows", "max_rows", "split_value")] + \
                [("gamma", ctypes.c_double), ("r_cr", ctypes.c_double)]
 
 

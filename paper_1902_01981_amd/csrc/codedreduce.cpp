@@ -69,6 +69,8 @@ struct cr_plan_s {
     const cr::Stage1Variant *variant_regs = nullptr, *variant_staged = nullptr;   // what exists for (x_dtype, d)
     int split_kind = -1;                            // -1: choose from the device when the workspace is sized
     int64_t split_value = 0;
+    int split_kind_used = -1;                       // what ensure_split settled on
+    int64_t split_value_used = 0;
     cr::Split split;
 
     // device binding
@@ -204,6 +206,8 @@ int ensure_split(cr_plan_t *p)
         p->variant = p->variant_staged;
     }
     const int teams_per_block = p->variant ? p->variant->teams_per_block() : 1;     // wide rows: one workgroup per piece
+    p->split_kind_used = kind;
+    p->split_value_used = value;
     if (kind == CR_SPLIT_ROW_CELLS || kind == CR_SPLIT_SHARED_CELLS) {
         if (p->row_visits / value + 2 * static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
         cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, kind == CR_SPLIT_SHARED_CELLS, p->split);
@@ -397,6 +401,12 @@ int cr_plan_info(const cr_plan_t *p, cr_plan_info_t *info)
     info->code_candidate = p->code.candidate;
     info->num_teams = p->split.teams;
     info->num_pieces = static_cast<int32_t>(p->split.pieces.size());
+    const bool split_known = !p->split.pieces.empty();
+    info->split_kind = split_known ? p->split_kind_used : -1;
+    info->split_value = split_known ? p->split_value_used : 0;
+    info->stage1_team_size = p->variant ? p->variant->team_size : 0;
+    info->stage1_teams_per_group = p->variant ? p->variant->teams_per_block() : 1;
+    info->stage1_staged = p->variant && p->variant->staged ? 1 : 0;
     info->m = p->m; info->d = p->d;
     info->row_visits = p->row_visits;
     info->min_rows = p->min_rows; info->max_rows = p->max_rows;

@@ -178,6 +178,7 @@ def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
     info = cr.cr_plan_info(p)
     assert info.num_pieces == len(slab) <= info.num_teams and np.all(np.diff(team) > 0)   # at most one piece per team
     assert np.all(pe > pb) and np.all(pe - pb <= cell_rows) and (pe - pb).sum() == info.row_visits
+    assert (info.split_kind, info.split_value, info.stage1_staged, info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, cell_rows, 1, per_group)
     for q in range(len(node)):                          # the pieces of a slab tile its row range
         idx = np.nonzero(slab == q)[0]
         idx = idx[np.argsort(pb[idx])]
