@@ -177,10 +177,14 @@ int cr_get_slab_grads(const cr_plan_t *plan, const float **G_dev); /* S x d */
 int cr_get_messages(const cr_plan_t *plan, const float **M_dev);   /* N x d, row = worker id */
 
 /* ---- timing ---------------------------------------------------------------------------------------------------------
- * With profiling enabled every kernel launch is bracketed by HIP events on the bound stream.  cr_profile_read waits for the
- * stream, then returns for one kernel id the summed duration, the number of launches and the algorithmic bytes of those launches
- * (bytes the method must move: rows read once per holder, each result written once) since profiling was enabled; any may be NULL. */
-int cr_profile_enable(cr_plan_t *plan, int enable);
+ * cr_profile_enable(plan, kernels): bit k of `kernels` set = every launch of kernel id k is bracketed by two HIP events on the
+ * bound stream from now on (CR_PROFILE_ALL: all of them, 0: none); a non-zero call also clears the totals.  Each bracket costs
+ * a few microseconds of device time, which shows on small problems.  cr_profile_read waits for the stream, then returns for one
+ * kernel id the summed duration, the number of launches and the algorithmic bytes of those launches (bytes the method must
+ * move: rows read once per holder, each result written once) since the last non-zero cr_profile_enable; any may be NULL.
+ * Totals read after cr_profile_enable(plan, 0) are those gathered until then. */
+#define CR_PROFILE_ALL ((1 << CR_K_COUNT) - 1)
+int cr_profile_enable(cr_plan_t *plan, int kernels);
 int cr_profile_read(cr_plan_t *plan, int kernel, double *total_ms, int64_t *launches, int64_t *algorithmic_bytes);
 /* algorithmic bytes of the most recent launch of a kernel id (0 if none yet) */
 int cr_last_algorithmic_bytes(const cr_plan_t *plan, int kernel, int64_t *bytes);

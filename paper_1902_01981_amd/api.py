@@ -19,6 +19,7 @@ CR_OK, CR_E_INVAL, CR_E_UNDECODABLE, CR_E_STATE, CR_E_HIP, CR_E_NOMEM = 0, -1, -
 CR_LINEAR, CR_LOGISTIC, CR_AGGREGATE_ONLY = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
 CR_K_PARTIAL_GRADS, CR_K_REDUCE_PIECES, CR_K_ENCODE, CR_K_DECODE, CR_K_UPDATE, CR_K_COUNT = 0, 1, 2, 3, 4, 5
+CR_PROFILE_ALL = (1 << CR_K_COUNT) - 1
 CR_SPLIT_EQUAL_RANGES, CR_SPLIT_ROW_CELLS, CR_SPLIT_SHARED_CELLS = 0, 1, 2
 DEFAULT_SEED = 190201981
 
@@ -242,8 +243,10 @@ def cr_get_messages(plan: int) -> int:
     return out.value
 
 
-def cr_profile_enable(plan: int, enable: bool) -> None:
-    _check(load_library().cr_profile_enable(plan, int(bool(enable))))
+def cr_profile_enable(plan: int, kernels) -> None:
+    """kernels: True = all, False = none, or a mask with bit k set for kernel id k."""
+    mask = (CR_PROFILE_ALL if kernels else 0) if isinstance(kernels, bool) else int(kernels)
+    _check(load_library().cr_profile_enable(plan, mask))
 
 
 def cr_profile_read(plan: int, kernel: int):

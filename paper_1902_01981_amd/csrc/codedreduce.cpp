@@ -96,7 +96,7 @@ struct cr_plan_s {
     bool have_grads = false, have_messages = false;
 
     // timing
-    bool profiling = false;
+    unsigned profiling = 0;                         // bit k: launches of kernel id k are bracketed by events
     std::vector<TimedLaunch> timed;
     std::vector<hipEvent_t> event_pool;
     double total_ms[CR_K_COUNT] = {};
@@ -289,14 +289,14 @@ struct LaunchTimer {     // brackets one launch with events when profiling is on
     LaunchTimer(cr_plan_t *plan, int k, int64_t bytes) : p(plan), kernel(k)
     {
         p->bytes_last[k] = bytes;
-        if (!p->profiling) return;
+        if (!((p->profiling >> k) & 1)) return;
         start = take_event(p);
         stop = take_event(p);
         if (start && stop) (void)hipEventRecord(start, p->stream);
     }
     void done()
     {
-        if (!p->profiling || !start || !stop) return;
+        if (!start || !stop) return;
         (void)hipEventRecord(stop, p->stream);
         p->timed.push_back({kernel, start, stop});
         p->bytes_sum[kernel] += p->bytes_last[kernel];
@@ -774,7 +774,7 @@ int cr_get_messages(const cr_plan_t *p, const float **M)
     return CR_OK;
 }
 
-int cr_profile_enable(cr_plan_t *p, int enable)
+int cr_profile_enable(cr_plan_t *p, int kernels)
 {
     if (!p) return fail(CR_E_INVAL, "NULL plan");
     if (p->bound) {
@@ -782,10 +782,11 @@ int cr_profile_enable(cr_plan_t *p, int enable)
         int rc = fold_timings(p);
         if (rc != CR_OK) return rc;
     }
-    if (enable && !p->profiling) {
+    if (kernels < 0 || kernels > CR_PROFILE_ALL) return fail(CR_E_INVAL, "kernel mask out of range");
+    if (kernels) {                                      // a new selection starts new totals
         for (int k = 0; k < CR_K_COUNT; ++k) { p->total_ms[k] = 0.0; p->launches[k] = 0; p->bytes_sum[k] = 0; }
     }
-    p->profiling = enable != 0;
+    p->profiling = static_cast<unsigned>(kernels);
     return CR_OK;
 }
 
