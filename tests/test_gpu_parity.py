@@ -405,3 +405,33 @@ def test_random_small_problems():
             mask[g * n + rng.choice(n, size=k, replace=False)] = 1
         _check_iteration(hip, orc, data["w0"], mask, TOL[x_dtype])
         hip.close()
+
+
+def test_random_sweep_of_staged_kernels():
+    """Seeded sweep over the staged stage-1 kernels: every chunk count of the one-wavefront family and of both four-wavefront
+    families, odd widths, trees with 2 to 27 holders per row, random cell heights, fewer than s stragglers in some groups."""
+    rng = np.random.default_rng(4242)
+    chunk_counts = list(range(257, 1025, 64)) + [1024, 1100, 1536, 1700, 2304, 2900, 3072]      # 16-byte chunks per row
+    for trial, nq in enumerate(chunk_counts):
+        L = int(rng.integers(1, 4))
+        n = int(rng.integers(2, 5))
+        s = int(rng.integers(1, n))
+        N = wl.num_workers(n, L)
+        d = 4 * nq - int(rng.integers(0, 4))              # any remainder modulo the chunk width
+        m = int(N * int(rng.integers(8, 40)) + rng.integers(0, max(60, 1_500_000 // d)))
+        model = cr.CR_LOGISTIC if trial % 2 else cr.CR_LINEAR
+        cfg = wl.config("cfg3" if model == cr.CR_LOGISTIC else "cfg2", L=L, n=n, s=s, m=m, d=d, model=model, x_dtype=cr.CR_F32,
+                        w0_std=None if model == cr.CR_LOGISTIC else 1.0, seed=5000 + trial)
+        data = wl.make_dataset(cfg)
+        split = (cr.CR_SPLIT_SHARED_CELLS, int(rng.integers(1, 60)))
+        print(f"trial {trial}: L={L} n={n} s={s} m={m} d={d} model={model} split={split}", flush=True)
+        hip = HipPath(L, n, s, data["X"], data["y"], model, cr.CR_F32, teams=split)
+        assert hip.info.stage1_staged == 1
+        orc = OraclePath(L, n, s, data["X"], data["y"], model)
+        mask = np.zeros(N, dtype=np.uint8)
+        for g in range(N // n):
+            k = int(rng.integers(0, s + 1))
+            mask[g * n + rng.choice(n, size=k, replace=False)] = 1
+        _check_iteration(hip, orc, data["w0"], mask, TOL[cr.CR_F32])
+        hip.close()
+
