@@ -113,11 +113,12 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *   CR_SPLIT_SHARED_CELLS  value = most rows per cell: the grid is laid between slab boundaries, so every holder of a cell holds
  *                          all of it; 2, 4 or 8 holders (by row width and by (s+1)^L, the most holders a row can have) share a
  *                          workgroup, which fetches each row once into LDS for all of them; each still does all of its own
- *                          arithmetic.  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.
+ *                          arithmetic.  One workgroup per compute unit works through a queue of cells (a team then runs
+ *                          several pieces).  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.
  * Default (when this is never called): with s = 0 (no row is held twice) equal ranges, one per resident workgroup; else shared
  * cells where that kernel exists and the problem has at least 128 rows per compute unit and workgroup, with the cell height
- * (64 to 1024 rows) whose list schedule over the chip's compute units ends first; else row cells of about 2 MB of X (96 to
- * 512 rows, fewer for small problems).  CR_E_STATE once a workspace is bound. */
+ * (64 to 1024 rows) that gives the shortest longest queue; else row cells of about 2 MB of X (96 to 512 rows, fewer for
+ * small problems).  CR_E_STATE once a workspace is bound. */
 enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1, CR_SPLIT_SHARED_CELLS = 2 };
 int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
 /* pieces in execution order: piece i is rows [row_begin[i], row_end[i]) of slab[i], run by team[i]; num_pieces entries each, any may be NULL */

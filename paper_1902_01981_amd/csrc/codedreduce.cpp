@@ -9,7 +9,6 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
-#include <queue>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -80,6 +79,7 @@ struct cr_plan_s {
     size_t ws_bytes = 0;
     cr::DevPiece *d_pieces = nullptr;
     int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr, *d_slab_pieces = nullptr;
+    int32_t *d_group_item_begin = nullptr, *d_item_pieces = nullptr;   // shared queues only
     char *d_program = nullptr;                     // per-call encode program + root decode terms
     size_t program_bytes = 0;
     float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr, *d_residuals = nullptr;   // residuals: wide-row path only
@@ -130,6 +130,16 @@ int group_decode_row(const cr_plan_t *p, const uint8_t *flags, const double **ro
 // MI355X has 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin by workgroup id.
 constexpr int kL2Domains = 8;
 
+// workgroup slots of the staged kernel = compute units of the current device (a multiple of the L2 domains); MI355X's 256 without one
+int unit_slots()
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kL2Domains)
+        return cus / kL2Domains * kL2Domains;
+    (void)hipGetLastError();
+    return 256;
+}
+
 int ensure_split(cr_plan_t *p)
 {
     if (!p->split.pieces.empty() || p->model == CR_AGGREGATE_ONLY) return CR_OK;
@@ -150,44 +160,18 @@ int ensure_split(cr_plan_t *p)
     }
     // small problems (under 128 rows per compute unit and workgroup) do not repay the staged kernel's start-up: row cells below
     if (kind < 0 && p->variant_staged && p->row_visits / p->variant_staged->teams_per_block() >= 256 * 128) {
-        // Rows staged through LDS: a workgroup occupies a compute unit alone and costs its rows plus a start-up of about 8 rows
-        // (pipeline fill, weights, the partial row it writes and the reduction reads back).  Workgroups are dealt to the 8 dies
-        // round-robin and each die gives the next one to its first free unit, so the time of a launch is the longest queue of that
-        // list schedule.  Take the cell height, 64 to 1024 rows, whose schedule ends first (measured: the ranking of the heights
-        // by this estimate is the ranking by run time on configurations 2 and 3); ties go to the taller cell.
+        // Rows staged through LDS: one workgroup per compute unit, each with a queue of cells (see split_shared_queues); the
+        // launch lasts as long as the longest queue.  Take the cell height, 64 to 1024 rows in steps of 8, that makes it
+        // shortest; ties go to the taller cell (fewer partial rows).
         kind = CR_SPLIT_SHARED_CELLS;
         const int tpb = p->variant_staged->teams_per_block();
-        int dev = 0, cus = 0;
-        if (!(hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kL2Domains)) {
-            (void)hipGetLastError();
-            cus = 256;
-        }
-        const int per_die = cus / kL2Domains;
-        value = 256;
-        if (p->row_visits / tpb / 64 <= (int64_t(1) << 17)) {       // beyond that the last round no longer matters
-            double best = -1.0;
+        value = 512;
+        if (p->row_visits / tpb / 64 <= (int64_t(1) << 16)) {       // with longer queues than that the last round no longer matters
+            int64_t best = -1;
             cr::Split trial;
-            for (int64_t c = 64; c <= 1024; c += 32) {
-                cr::split_row_cells(p->slabs, c, kL2Domains, tpb, true, trial);
-                std::vector<std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>>> die(kL2Domains);
-                for (auto &q : die)
-                    for (int u = 0; u < per_die; ++u) q.push(0);
-                int64_t end = 0;
-                for (int g = 0; g * tpb < trial.teams; ++g) {
-                    int64_t rows = 0;
-                    for (int t = g * tpb; t < std::min(trial.teams, (g + 1) * tpb) && rows == 0; ++t)
-                        if (trial.team_piece_begin[t + 1] > trial.team_piece_begin[t]) {
-                            const cr::Piece &pc = trial.pieces[trial.team_piece_begin[t]];
-                            rows = pc.row_end - pc.row_begin;
-                        }
-                    if (rows == 0) continue;                         // a workgroup without work leaves at once
-                    auto &q = die[g % kL2Domains];
-                    const int64_t done = q.top() + rows + 8;
-                    q.pop();
-                    q.push(done);
-                    end = std::max(end, done);
-                }
-                if (best < 0.0 || static_cast<double>(end) <= best) { best = static_cast<double>(end); value = c; }
+            for (int64_t c = 64; c <= 1024; c += 8) {
+                cr::split_shared_queues(p->slabs, c, kL2Domains, tpb, unit_slots() / kL2Domains, trial);
+                if (best < 0 || trial.makespan <= best) { best = trial.makespan; value = c; }
             }
         }
     }
@@ -208,29 +192,31 @@ int ensure_split(cr_plan_t *p)
     const int teams_per_block = p->variant ? p->variant->teams_per_block() : 1;     // wide rows: one workgroup per piece
     p->split_kind_used = kind;
     p->split_value_used = value;
-    if (kind == CR_SPLIT_ROW_CELLS || kind == CR_SPLIT_SHARED_CELLS) {
+    if (kind == CR_SPLIT_SHARED_CELLS) {
         if (p->row_visits / value + 2 * static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, kind == CR_SPLIT_SHARED_CELLS, p->split);
+        cr::split_shared_queues(p->slabs, value, kL2Domains, teams_per_block, unit_slots() / kL2Domains, p->split);
+        // what the staged kernel relies on: every piece of an item covers the same rows
+        const cr::Split &sp = p->split;
+        for (size_t it = 0; it * teams_per_block < sp.item_pieces.size(); ++it) {
+            const cr::Piece *first = nullptr;
+            for (int t = 0; t < teams_per_block; ++t) {
+                const int32_t pi = sp.item_pieces[it * teams_per_block + t];
+                if (pi < 0) continue;
+                const cr::Piece &pc = sp.pieces[pi];
+                if (first && (first->row_begin != pc.row_begin || first->row_end != pc.row_end)) {
+                    p->split = cr::Split();
+                    return fail(CR_E_STATE, "shared cells: the teams of a workgroup do not hold the same rows");
+                }
+                if (!first) first = &pc;
+            }
+        }
+    } else if (kind == CR_SPLIT_ROW_CELLS) {
+        if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
+        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, p->split);
         if (!p->variant) {                                  // the wide-row kernels index pieces directly: no empty teams
             cr::Split compact;
-            cr::split_row_cells(p->slabs, value, 1, 1, false, compact);
+            cr::split_row_cells(p->slabs, value, 1, 1, compact);
             p->split = compact;
-        }
-        if (kind == CR_SPLIT_SHARED_CELLS) {
-            // what the staged kernel relies on: at most one piece per team, and the same rows for every team of a workgroup
-            for (int g = 0; g * teams_per_block < p->split.teams; ++g) {
-                const cr::Piece *first = nullptr;
-                for (int t = g * teams_per_block; t < std::min(p->split.teams, (g + 1) * teams_per_block); ++t) {
-                    const int32_t pb = p->split.team_piece_begin[t], pe = p->split.team_piece_begin[t + 1];
-                    if (pe == pb) continue;
-                    const cr::Piece &pc = p->split.pieces[pb];
-                    if (pe - pb > 1 || (first && (first->row_begin != pc.row_begin || first->row_end != pc.row_end))) {
-                        p->split = cr::Split();
-                        return fail(CR_E_STATE, "shared cells: the teams of a workgroup do not hold the same rows");
-                    }
-                    if (!first) first = &pc;
-                }
-            }
         }
     } else {
         const int teams = static_cast<int>(std::min<int64_t>(value, std::max<int64_t>(1, p->row_visits)));
@@ -259,6 +245,8 @@ void compute_layout(cr_plan_t *p, size_t *total)
     w = align_up(w + (p->split.teams + 1) * sizeof(int32_t), 256);
     w = align_up(w + (S + 1) * sizeof(int32_t), 256);
     w = align_up(w + P * sizeof(int32_t), 256);
+    w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
+    w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
     w = align_up(w + p->program_bytes, 256);
     const size_t row = static_cast<size_t>(p->d) * sizeof(float);
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -532,6 +520,8 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     p->d_team_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (p->split.teams + 1) * sizeof(int32_t), 256);
     p->d_slab_piece_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + (S + 1) * sizeof(int32_t), 256);
     p->d_slab_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + P * sizeof(int32_t), 256);
+    p->d_group_item_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
+    p->d_item_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
     p->d_program = p->ws + w;                                              w = align_up(w + p->program_bytes, 256);
     p->d_partial = nullptr; p->d_G = nullptr;
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -554,6 +544,10 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
         CR_HIP(hipMemcpy(p->d_team_piece_begin, p->split.team_piece_begin.data(), (p->split.teams + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
         CR_HIP(hipMemcpy(p->d_slab_piece_begin, p->split.slab_piece_begin.data(), (S + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
         CR_HIP(hipMemcpy(p->d_slab_pieces, p->split.slab_pieces.data(), P * sizeof(int32_t), hipMemcpyHostToDevice));
+        if (!p->split.item_pieces.empty()) {
+            CR_HIP(hipMemcpy(p->d_group_item_begin, p->split.group_item_begin.data(), p->split.group_item_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+            CR_HIP(hipMemcpy(p->d_item_pieces, p->split.item_pieces.data(), p->split.item_pieces.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+        }
     }
     if (!p->h_staging) {
         CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kStagingSlots, hipHostMallocDefault));
@@ -576,7 +570,11 @@ int cr_partial_grads(cr_plan_t *p, const void *X, const float *y, const float *w
         // what the method must move: every holder reads its rows and targets once, each slab gradient is written once
         const int64_t bytes = p->row_visits * p->d * elem_size(p) + p->row_visits * 4 + S * p->d * 4 + p->d * 4;
         LaunchTimer t(p, CR_K_PARTIAL_GRADS, bytes);
-        if (p->variant) {
+        if (p->variant && p->variant->staged) {
+            CR_HIP(cr::launch_partial_grads_staged(*p->variant, X, y, w, p->d_pieces, p->d_group_item_begin, p->d_item_pieces,
+                                                   static_cast<int>(p->split.group_item_begin.size()) - 1, p->d_partial, p->d,
+                                                   p->model == CR_LOGISTIC ? 1 : 0, p->stream));
+        } else if (p->variant) {
             CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->split.teams, p->d_partial, p->d,
                                             p->model == CR_LOGISTIC ? 1 : 0, p->stream));
         } else {

@@ -56,6 +56,11 @@ hipError_t prepare_stage1(const Stage1Variant &v);
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
                                 hipStream_t stream);
+// Staged variants: workgroup g works through items [group_item_begin[g], group_item_begin[g+1]); item i hands team t of the
+// workgroup the piece item_pieces[i * teams_per_block + t] (or -1); all pieces of an item cover the same rows.
+hipError_t launch_partial_grads_staged(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
+                                       const int32_t *group_item_begin, const int32_t *item_pieces, int num_groups, float *partial,
+                                       int64_t d, int logistic, hipStream_t stream);
 // Wide rows (a row does not fit the registers of one team): two passes.  launch_residuals writes phi(x.w) - y for every row visit,
 // launch_xt_residuals forms X^T r per piece and block of 256*kWideChunks*vec columns.  X is read twice on this path.
 constexpr int kWideChunks = 8;

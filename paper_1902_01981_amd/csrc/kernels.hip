@@ -262,12 +262,13 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 // exactly as above.  The L2 therefore serves a row once per workgroup instead of once per holder.
 // Software pipeline, one barrier per step of R rows: while step s is computed from one LDS buffer, step s+1 moves from registers
 // into the other buffer and the global loads of steps s+2 and s+3 are in flight in two register sets.
-// All teams of the workgroup must hold the same rows (cells cut at slab boundaries) and at most one piece each.
+// One workgroup per compute unit works through a queue of items (an item = one cell for up to H of its holders); all pieces of
+// an item must cover the same rows (cells cut at slab boundaries).  The weights are loaded once per workgroup.
 template <int XD, int VEC, int TS, int K, int R, int H, bool LOGISTIC>
 __global__ void __launch_bounds__(TS * H)
 partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
-                            const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
-                            float *__restrict__ partial, int d, int nq)
+                            const DevPiece *__restrict__ pieces, const int32_t *__restrict__ group_item_begin,
+                            const int32_t *__restrict__ item_pieces, float *__restrict__ partial, int d, int nq)
 {
     using C = Chunk<XD, VEC>;
     using raw_t = typename C::raw_t;
@@ -280,23 +281,11 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
     const int tib = __builtin_amdgcn_readfirstlane(threadIdx.x / TS);
     const int wave = tl / 64;
 
-    // the rows of this workgroup are those of its first team that has a piece
-    int my_piece = -1, ref_piece = -1;
-#pragma unroll
-    for (int t = 0; t < H; ++t) {
-        const int team = blockIdx.x * H + t;
-        if (team < num_teams) {
-            const int pb = team_piece_begin[team];
-            if (team_piece_begin[team + 1] > pb) {
-                if (ref_piece < 0) ref_piece = pb;
-                if (t == tib) my_piece = pb;
-            }
-        }
-    }
-    if (ref_piece < 0) return;                          // the whole workgroup leaves: no barrier has been reached yet
-    const DevPiece pc = pieces[ref_piece];
-    const bool active = my_piece >= 0;                  // a team without a piece only helps to fetch
-    const int nsteps = (pc.nrows + R - 1) / R;
+    // what the item in hand is: set at the top of the item loop below, read by the pipeline stages
+    DevPiece pc = {};                                   // the rows of the item (every team's piece of it has the same rows)
+    int my_piece = -1;                                  // this team's piece of the item, or -1: it then only helps to fetch
+    bool active = false;
+    int nsteps = 0;
 
     // fetch role: thread g of the workgroup brings chunks g, g+BT, ... of every row
     unsigned goff[LPT];
@@ -315,10 +304,6 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
         }
     }
     float acc[K][VEC];
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
 
     auto fetch = [&](raw_t (&P)[R][LPT], int step) {
 #pragma unroll
@@ -391,24 +376,48 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
         }
     };
 
+    // The workgroup works through its queue of items.  The last barrier of an item is behind every LDS read of it, so the next
+    // item's first buffer can be filled at once; loads still in flight for steps past its end land in registers nobody reads.
     raw_t P0[R][LPT], P1[R][LPT];
-    fetch(P0, 0);
-    fetch(P1, 1);                                       // steps past the end re-read the last row; nothing is computed from them
-    park(P0, 0);
-    fetch(P0, 2);
-    __syncthreads();
-    int step = 0;
-    for (; step + 1 < nsteps; step += 2) {              // two steps per trip, so that register sets and LDS buffers are fixed at compile time
-        step_fn(step, P1, 0);
-        step_fn(step + 1, P0, 1);
-    }
-    if (step < nsteps) step_fn(step, P1, 0);
-    if (active) {
-        float *out = partial + static_cast<int64_t>(my_piece) * d;
+    const int item_end = group_item_begin[blockIdx.x + 1];
+    for (int item = group_item_begin[blockIdx.x]; item < item_end; ++item) {
+        int ref_piece = -1;
+        my_piece = -1;
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int q = tl + k * TS;
-            if (q < nq) store_row<VEC>(out + chunk_offset<VEC>(q, nq, d), acc[k]);
+        for (int t = 0; t < H; ++t) {
+            const int pi = item_pieces[item * H + t];
+            if (pi >= 0) {
+                if (ref_piece < 0) ref_piece = pi;
+                if (t == tib) my_piece = pi;
+            }
+        }
+        if (ref_piece < 0) continue;                    // a gap in the queue (the same for the whole workgroup)
+        pc = pieces[ref_piece];
+        active = my_piece >= 0;
+        nsteps = (pc.nrows + R - 1) / R;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
+
+        fetch(P0, 0);
+        fetch(P1, 1);                                   // steps past the end re-read the last row; nothing is computed from them
+        park(P0, 0);
+        fetch(P0, 2);
+        __syncthreads();
+        int step = 0;
+        for (; step + 1 < nsteps; step += 2) {          // two steps per trip, so that register sets and LDS buffers are fixed at compile time
+            step_fn(step, P1, 0);
+            step_fn(step + 1, P0, 1);
+        }
+        if (step < nsteps) step_fn(step, P1, 0);
+        if (active) {
+            float *out = partial + static_cast<int64_t>(my_piece) * d;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int q = tl + k * TS;
+                if (q < nq) store_row<VEC>(out + chunk_offset<VEC>(q, nq, d), acc[k]);
+            }
         }
     }
 }
@@ -805,6 +814,17 @@ hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const flo
     void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq};
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
+    return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, 0, stream);
+}
+
+hipError_t launch_partial_grads_staged(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
+                                       const int32_t *group_item_begin, const int32_t *item_pieces, int num_groups, float *partial,
+                                       int64_t d, int logistic, hipStream_t stream)
+{
+    int di = static_cast<int>(d);
+    int nq = static_cast<int>((d + v.vec - 1) / v.vec);
+    void *args[] = {&X, &y, &w, &pieces, &group_item_begin, &item_pieces, &partial, &di, &nq};
+    dim3 grid(num_groups), block(v.block());
     return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, v.lds_bytes(), stream);
 }
 

@@ -159,39 +159,121 @@ void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out)
     index_slab_pieces(slabs.size(), out);
 }
 
-void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, bool whole_cells, Split &out)
+namespace {
+struct Unit { int64_t cell; int32_t slab; int64_t row_begin, row_end; };
+
+// Cells that every holder holds whole: the row axis is first cut wherever any slab begins or ends (between two such cuts the set of
+// holders does not change), then every stretch is cut into near-equal cells of at most cell_rows rows.  Units sorted by cell.
+std::vector<Unit> whole_cell_units(const std::vector<Slab> &slabs, int64_t cell_rows)
 {
-    struct Unit { int64_t cell; int32_t slab; int64_t row_begin, row_end; };
     std::vector<Unit> units;
-    if (!whole_cells) {
-        for (size_t q = 0; q < slabs.size(); ++q) {
-            int64_t b = slabs[q].row_begin;
-            while (b < slabs[q].row_end) {
-                const int64_t cell = b / cell_rows;
-                const int64_t e = std::min(slabs[q].row_end, (cell + 1) * cell_rows);
-                units.push_back({cell, static_cast<int32_t>(q), b, e});
-                b = e;
+    std::vector<int64_t> cuts;
+    cuts.reserve(2 * slabs.size());
+    for (const Slab &sl : slabs) { cuts.push_back(sl.row_begin); cuts.push_back(sl.row_end); }
+    std::sort(cuts.begin(), cuts.end());
+    cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+    std::vector<int64_t> first_cell(cuts.size(), 0);     // index of the first cell of the stretch that starts at cuts[i]
+    for (size_t i = 0; i + 1 < cuts.size(); ++i) first_cell[i + 1] = first_cell[i] + (cuts[i + 1] - cuts[i] + cell_rows - 1) / cell_rows;
+    for (size_t q = 0; q < slabs.size(); ++q) {
+        size_t i = static_cast<size_t>(std::lower_bound(cuts.begin(), cuts.end(), slabs[q].row_begin) - cuts.begin());
+        for (; i + 1 < cuts.size() && cuts[i] < slabs[q].row_end; ++i) {
+            const int64_t len = cuts[i + 1] - cuts[i];
+            const int64_t parts = (len + cell_rows - 1) / cell_rows;
+            for (int64_t c = 0; c < parts; ++c)
+                units.push_back({first_cell[i] + c, static_cast<int32_t>(q), cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * c / parts),
+                                 cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * (c + 1) / parts)});
+        }
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.cell < b.cell; });
+    return units;
+}
+}  // namespace
+
+void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_group, int slots_per_lane, Split &out)
+{
+    const std::vector<Unit> units = whole_cell_units(slabs, cell_rows);
+    // an item = up to teams_per_group holders of one cell = the work of one workgroup for the length of that cell
+    struct Item { size_t ub, ue; };                          // units [ub, ue)
+    struct Cell { std::vector<Item> items; };
+    std::vector<Cell> cells;
+    size_t widest = 1;
+    for (size_t i = 0; i < units.size();) {
+        size_t k = i;
+        while (k < units.size() && units[k].cell == units[i].cell) ++k;
+        Cell c;
+        for (size_t u = i; u < k; u += teams_per_group) c.items.push_back({u, std::min(k, u + teams_per_group)});
+        widest = std::max(widest, c.items.size());
+        cells.push_back(std::move(c));
+        i = k;
+    }
+    // A gang = `gang` workgroup slots of one L2 domain that work through the same sequence of rounds side by side.  A round holds
+    // cells whose items fill at most the gang (one item per slot), so all workgroups that share a cell run it at the same time,
+    // from the first round on.  Cells with more items than a domain has slots are spread over several rounds.
+    const size_t gang = std::min(widest, static_cast<size_t>(slots_per_lane));
+    const size_t gangs = static_cast<size_t>(lanes) * (slots_per_lane / gang);
+    struct Round { std::vector<Item> slot; };                // slot[j] = the item of gang slot j (ub == ue: none)
+    std::vector<Round> rounds;
+    for (const Cell &c : cells)
+        for (size_t first = 0; first < c.items.size(); first += gang) {
+            const size_t count = std::min(gang, c.items.size() - first);
+            if (rounds.empty() || rounds.back().slot.size() + count > gang) rounds.push_back({});
+            for (size_t j = 0; j < count; ++j) rounds.back().slot.push_back(c.items[first + j]);
+        }
+    // round r goes to gang r mod gangs: consecutive cells land on different L2 domains and every gang gets the same number of rounds
+    // to within one.  Gang g = (domain x = g mod lanes, number k = g / lanes) occupies workgroup ids x + lanes*(k*gang + j), j < gang.
+    const size_t groups_all = static_cast<size_t>(lanes) * (slots_per_lane / gang) * gang;
+    std::vector<std::vector<Item>> queue(groups_all);
+    for (size_t r = 0; r < rounds.size(); ++r) {
+        const size_t g = r % gangs, x = g % lanes, k = g / lanes;
+        for (size_t j = 0; j < gang; ++j)
+            queue[x + lanes * (k * gang + j)].push_back(j < rounds[r].slot.size() ? rounds[r].slot[j] : Item{0, 0});
+    }
+    size_t groups = groups_all;
+    auto empty_queue = [&](const std::vector<Item> &q) { return std::all_of(q.begin(), q.end(), [](const Item &it) { return it.ub == it.ue; }); };
+    while (groups > 0 && empty_queue(queue[groups - 1])) --groups;
+
+    out = Split();
+    out.teams = static_cast<int>(groups) * teams_per_group;
+    out.team_piece_begin.assign(out.teams + 1, 0);
+    out.group_item_begin.assign(groups + 1, 0);
+    // pieces team-major (a team's pieces are contiguous, in the order it runs them); then the item table that points at them
+    std::vector<std::vector<int32_t>> piece_of(groups);      // per group: items x teams_per_group, piece index or -1
+    for (size_t g = 0; g < groups; ++g) {
+        piece_of[g].assign(queue[g].size() * teams_per_group, -1);
+        for (int t = 0; t < teams_per_group; ++t) {
+            const int32_t team = static_cast<int32_t>(g) * teams_per_group + t;
+            out.team_piece_begin[team] = static_cast<int32_t>(out.pieces.size());
+            for (size_t i = 0; i < queue[g].size(); ++i) {
+                const Item &it = queue[g][i];
+                if (it.ub + t >= it.ue) continue;
+                const Unit &u = units[it.ub + t];
+                piece_of[g][i * teams_per_group + t] = static_cast<int32_t>(out.pieces.size());
+                out.pieces.push_back({u.slab, team, u.row_begin, u.row_end});
             }
         }
-    } else {
-        // Cells that every holder holds whole: the row axis is first cut wherever any slab begins or ends (between two such cuts
-        // the set of holders does not change), then every stretch is cut into near-equal cells of at most cell_rows rows.
-        std::vector<int64_t> cuts;
-        cuts.reserve(2 * slabs.size());
-        for (const Slab &sl : slabs) { cuts.push_back(sl.row_begin); cuts.push_back(sl.row_end); }
-        std::sort(cuts.begin(), cuts.end());
-        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
-        std::vector<int64_t> first_cell(cuts.size(), 0);     // index of the first cell of the stretch that starts at cuts[i]
-        for (size_t i = 0; i + 1 < cuts.size(); ++i) first_cell[i + 1] = first_cell[i] + (cuts[i + 1] - cuts[i] + cell_rows - 1) / cell_rows;
-        for (size_t q = 0; q < slabs.size(); ++q) {
-            size_t i = static_cast<size_t>(std::lower_bound(cuts.begin(), cuts.end(), slabs[q].row_begin) - cuts.begin());
-            for (; i + 1 < cuts.size() && cuts[i] < slabs[q].row_end; ++i) {
-                const int64_t len = cuts[i + 1] - cuts[i];
-                const int64_t parts = (len + cell_rows - 1) / cell_rows;
-                for (int64_t c = 0; c < parts; ++c)
-                    units.push_back({first_cell[i] + c, static_cast<int32_t>(q), cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * c / parts),
-                                     cuts[i] + static_cast<int64_t>(static_cast<__int128>(len) * (c + 1) / parts)});
-            }
+        int64_t busy = 0;
+        for (const Item &it : queue[g])
+            if (it.ub < it.ue) busy += units[it.ub].row_end - units[it.ub].row_begin + 4;     // + pipeline refill and the partial row, in rows
+        out.makespan = std::max(out.makespan, busy);
+    }
+    out.team_piece_begin[out.teams] = static_cast<int32_t>(out.pieces.size());
+    for (size_t g = 0; g < groups; ++g) {
+        out.group_item_begin[g + 1] = out.group_item_begin[g] + static_cast<int32_t>(queue[g].size());
+        out.item_pieces.insert(out.item_pieces.end(), piece_of[g].begin(), piece_of[g].end());
+    }
+    index_slab_pieces(slabs.size(), out);
+}
+
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out)
+{
+    std::vector<Unit> units;
+    for (size_t q = 0; q < slabs.size(); ++q) {
+        int64_t b = slabs[q].row_begin;
+        while (b < slabs[q].row_end) {
+            const int64_t cell = b / cell_rows;
+            const int64_t e = std::min(slabs[q].row_end, (cell + 1) * cell_rows);
+            units.push_back({cell, static_cast<int32_t>(q), b, e});
+            b = e;
         }
     }
     std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.cell < b.cell; });

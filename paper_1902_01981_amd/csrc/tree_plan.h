@@ -52,6 +52,11 @@ struct Split {
     std::vector<int32_t> slab_piece_begin;   // S + 1
     std::vector<int32_t> slab_pieces;        // one entry per piece
     int teams = 0;
+    // shared queues only: workgroup g runs items [group_item_begin[g], group_item_begin[g+1]) in order; item i gives every team
+    // of the workgroup its piece, item_pieces[i * teams_per_group + t], or -1
+    std::vector<int32_t> group_item_begin;
+    std::vector<int32_t> item_pieces;
+    int64_t makespan = 0;                    // longest queue, in rows (with a few rows of start-up per item)
 };
 
 // Equal ranges: the slab-major row-visit space is cut into `teams` equal contiguous ranges, cut again at slab boundaries.
@@ -61,8 +66,12 @@ void split_equal_ranges(const std::vector<Slab> &slabs, int teams, Split &out);
 // that the holders of the same rows are launched together and stream the same addresses at the same time (all but the first of them
 // are then served by the L2 cache instead of HBM).  `lanes` = number of L2 domains workgroups are dealt to round-robin,
 // `teams_per_block` = teams in one workgroup: the holders of a cell go to workgroup ids congruent modulo `lanes`.
-// With `whole_cells` the grid is laid inside the stretches between slab boundaries instead (cells of at most `cell_rows` rows),
-// so that every holder of a cell holds all of it: the teams of one workgroup then work on identical row ranges.
-void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, bool whole_cells, Split &out);
+void split_row_cells(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_block, Split &out);
+
+// Shared queues: cells are laid inside the stretches between slab boundaries (at most `cell_rows` rows, near-equal), so that every
+// holder of a cell holds all of it.  Up to `teams_per_group` holders of a cell form an item, the work of one workgroup; there are
+// lanes * slots_per_lane workgroup slots (one per compute unit), each with a queue of items.  All items of a cell sit at the same
+// position of the queues of neighbouring slots of one L2 domain, so they run side by side from the start of the launch.
+void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int lanes, int teams_per_group, int slots_per_lane, Split &out);
 
 }  // namespace cr

@@ -170,13 +170,14 @@ def test_row_cell_split(plans, cell_rows):
                                                   (1, 5, 2, 4_001, 3_001, 4), (2, 3, 1, 1_111, 1_028, 4)])
 @pytest.mark.parametrize("cell_rows", [1, 7, 50, 10 ** 6])
 def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
-    """Cells laid between slab boundaries: every team of a workgroup (per_group teams) holds exactly the same rows."""
+    """Cells laid between slab boundaries and queued on at most 256 workgroups of per_group teams: the holders of a cell sit in
+    neighbouring workgroups of one L2 domain, per_group of them per workgroup, and hold exactly the same rows."""
     p = plans(L, n, s, m, d)
     cr.cr_plan_set_split(p, cr.CR_SPLIT_SHARED_CELLS, cell_rows)
     node, rb, re_, _ = cr.cr_plan_get_slabs(p)
     slab, pb, pe, team = cr.cr_plan_get_pieces(p)
     info = cr.cr_plan_info(p)
-    assert info.num_pieces == len(slab) <= info.num_teams and np.all(np.diff(team) > 0)   # at most one piece per team
+    assert info.num_pieces == len(slab) and info.num_teams <= 256 * per_group and np.all(np.diff(team) >= 0)
     assert np.all(pe > pb) and np.all(pe - pb <= cell_rows) and (pe - pb).sum() == info.row_visits
     assert (info.split_kind, info.split_value, info.stage1_staged, info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, cell_rows, 1, per_group)
     for q in range(len(node)):                          # the pieces of a slab tile its row range
@@ -185,23 +186,25 @@ def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
         assert pb[idx[0]] == rb[q] and pe[idx[-1]] == re_[q] and np.array_equal(pb[idx[1:]], pe[idx[:-1]])
     group = team // per_group
     cuts = np.unique(np.concatenate([rb, re_]))
-    ranges = {}
+    cell_end, cell_groups, cell_count = {}, {}, {}
     for g, b, e in zip(group, pb, pe):
-        assert ranges.setdefault(g, (b, e)) == (b, e), g            # one row range per workgroup
+        assert cell_end.setdefault(b, e) == e                        # every holder of a cell holds all of it
         i = np.searchsorted(cuts, b, side="right")
         assert cuts[i - 1] <= b and e <= cuts[i]                     # no slab begins or ends inside a cell
-    holders = {}
-    for g, b in zip(group, pb):
-        holders.setdefault(b, set()).add(g % 8)
-    assert all(len(v) == 1 for v in holders.values())                # all workgroups of a cell sit on one L2 domain
-    # a holder count of h needs ceil(h / per_group) workgroups
-    count = {}
-    for b in pb:
-        count[b] = count.get(b, 0) + 1
-    groups_per_cell = {}
-    for g, b in set(zip(group, pb)):
-        groups_per_cell[b] = groups_per_cell.get(b, 0) + 1
-    assert all(groups_per_cell[b] == -(-count[b] // per_group) for b in count)
+        cell_groups.setdefault(b, set()).add(g)
+        cell_count[b] = cell_count.get(b, 0) + 1
+    for b, gs in cell_groups.items():
+        gs = sorted(gs)
+        assert len(set(g % 8 for g in gs)) == 1                      # one L2 domain
+        assert len(gs) == -(-cell_count[b] // per_group)             # h holders need ceil(h / per_group) workgroups ...
+        assert all(y - x == 8 for x, y in zip(gs, gs[1:])) or len(gs) > 32     # ... neighbouring slots of that domain
+    # a team never holds two pieces of the same rows, and the queues are level: no workgroup has much more than its share
+    assert len(set(zip(team, pb))) == len(team)
+    work = {}
+    for g, b, e in set(zip(group, pb, pe)):                          # a workgroup runs a cell once, for all of its teams
+        work[g] = work.get(g, 0) + (e - b)
+    busy = np.array(list(work.values()), dtype=np.float64)
+    assert busy.max() <= 1.25 * busy.mean() + 2 * (pe - pb).max()
 
 
 def test_shared_cells_need_a_staged_kernel(plans):
