@@ -124,6 +124,8 @@ CASES = [
     ("staged-3-holders", 1, 5, 2, 4_001, 3_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 100)),      # one idle team per workgroup of four
     ("staged-k12", 2, 3, 1, 900, 12_288, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 1000)),            # the widest staged rows
     ("staged-default", 2, 4, 1, 140_000, 1_100, cr.CR_LINEAR, cr.CR_F32, None),                               # large enough for the staged default
+    ("staged-queue-gaps", 3, 2, 1, 3_000, 7_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 40)),      # cells of 1, 2 and 4 workgroups in gangs of 4
+    ("staged-wide-gang", 4, 3, 2, 2_400, 6_200, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 25)),     # 81 holders: more workgroups per cell than one L2 domain has slots
 ]
 
 
