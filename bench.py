@@ -3,7 +3,7 @@
 
 One "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
 host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> cr_gd_update
-(issued through cr_gd_run, which enqueues exactly these calls for every step).
+(issued through cr_gd_run, which enqueues these steps for every mask; the gradient step rides in the decode launch).
 Prints ONE JSON line: iterations/s, the roofline of the dominant kernel (measured live with HIP events on the
 library's stream, over the timed steps) and the CPU oracle timed on a bounded sample of the same workload.  The other
 kernels' averages come from a few more steps after the timed region ("timed_region": false in the "kernels" table).

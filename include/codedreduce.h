@@ -169,7 +169,8 @@ int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
  *   w_dev, g_dev    d floats each; w is updated in place, g holds the last decoded gradient
  *   w_star_or_null  d floats (device): the reference model of the normalised error rate, or NULL
  *   metrics_or_null device, steps x 2 floats: [2t] = ||w_t+1 - w_t||^2 / ||w_t||^2 (relative error rate, eq. (6)),
- *                   [2t+1] = ||w_t+1 - w*||^2 / ||w*||^2 (normalised error rate, eq. (8); -1 without w*); NULL = plain update */
+ *                   [2t+1] = ||w_t+1 - w*||^2 / ||w*||^2 (normalised error rate, eq. (8); -1 without w*); NULL = plain update,
+ *                   which then rides in the decode launch (the same arithmetic as cr_gd_update, one launch fewer per step) */
 int cr_gd_run(cr_plan_t *plan, const void *X_dev, const float *y_dev, float *w_dev, float *g_dev, const uint8_t *masks_host,
               int steps, float lr, const float *w_star_or_null, float *metrics_or_null);
 

@@ -702,16 +702,22 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     return CR_OK;
 }
 
-int cr_decode_root(cr_plan_t *p, float *g)
+namespace {
+// the master's decode; with w != nullptr the gradient step w <- w - lr g rides in the same launch
+int decode_root(cr_plan_t *p, float *g, float *w, float lr)
 {
     if (!p || !g) return fail(CR_E_INVAL, "NULL argument");
     if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
     if (!p->have_messages) return fail(CR_E_STATE, "no messages yet: call cr_encode_tree first");
-    LaunchTimer t(p, CR_K_DECODE, static_cast<int64_t>(p->num_dec_terms + 1) * p->d * 4);
-    CR_HIP(cr::launch_decode(p->d_M, g, reinterpret_cast<const cr::DecTerm *>(p->d_program + p->off_dec), p->num_dec_terms, p->d, p->stream));
+    LaunchTimer t(p, CR_K_DECODE, static_cast<int64_t>(p->num_dec_terms + 1 + (w ? 2 : 0)) * p->d * 4);
+    CR_HIP(cr::launch_decode(p->d_M, g, reinterpret_cast<const cr::DecTerm *>(p->d_program + p->off_dec), p->num_dec_terms, p->d, w, lr,
+                             p->stream));
     t.done();
     return CR_OK;
 }
+}  // namespace
+
+int cr_decode_root(cr_plan_t *p, float *g) { return decode_root(p, g, nullptr, 0.f); }
 
 int cr_gd_update(cr_plan_t *p, float *w, const float *g, float lr)
 {
@@ -742,15 +748,13 @@ int cr_gd_run(cr_plan_t *p, const void *X, const float *y, float *w, float *g, c
     for (int t = 0; t < steps; ++t) {
         int rc = cr_partial_grads(p, X, y, w);
         if (rc == CR_OK) rc = cr_encode_tree(p, masks + static_cast<size_t>(t) * N);
-        if (rc == CR_OK) rc = cr_decode_root(p, g);
+        // without the convergence measures the gradient step rides in the decode launch (same arithmetic as cr_gd_update)
+        if (rc == CR_OK) rc = decode_root(p, g, metrics ? nullptr : w, lr);
         if (rc != CR_OK) return rc;
         if (metrics) {
             LaunchTimer tm(p, CR_K_UPDATE, 3 * p->d * 4 + (w_star ? p->d * 4 : 0));
             CR_HIP(cr::launch_update_metrics(w, g, lr, w_star, metrics + 2 * static_cast<size_t>(t), p->d, p->stream));
             tm.done();
-        } else {
-            rc = cr_gd_update(p, w, g, lr);
-            if (rc != CR_OK) return rc;
         }
     }
     return CR_OK;

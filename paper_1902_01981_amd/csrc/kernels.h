@@ -71,7 +71,8 @@ hipError_t launch_xt_residuals(int x_dtype, const void *X, const DevPiece *piece
 hipError_t launch_reduce_pieces(const float *partial, const int32_t *slab_piece_begin, const int32_t *slab_pieces, int num_slabs, float *G, int64_t d,
                                 hipStream_t stream);
 hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int num_sub, int L, int64_t d, hipStream_t stream);
-hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream);
+// w != nullptr: also steps w <- w - lr g (g as stored, rounded to fp32) in the same launch
+hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, float *w, float lr, hipStream_t stream);
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream);
 hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream);
 

@@ -6,7 +6,7 @@
 //   residuals_kernel, xt_residuals_kernel   the same in two passes, for rows too wide for one team's registers
 //   reduce_pieces_kernel   sums the pieces of each slab (fixed order, so results are reproducible bit for bit)
 //   encode_kernel          CR.Execute steps 2-5: every node's message, children folded into parents in registers
-//   decode_kernel          the master's decode  g = sum_j a_j m_(1,j)
+//   decode_kernel          the master's decode  g = sum_j a_j m_(1,j), optionally followed by w <- w - lr g in the same launch
 //   update_kernel, update_metrics_kernel    w <- w - lr g, optionally with the convergence measures of eq. (6) and (8)
 //
 // Rows of d elements start on a 4-byte (fp32) or 2-byte (bf16) boundary whatever d is, so the 16-byte row accesses are declared
@@ -651,7 +651,8 @@ encode_kernel(const float *__restrict__ G, float *__restrict__ M, EncProgram pro
 // ---- decode ---------------------------------------------------------------------------------------------------------
 template <int VEC>
 __global__ void __launch_bounds__(256)
-decode_kernel(const float *__restrict__ M, float *__restrict__ g, const DecTerm *__restrict__ terms, int nterms, int64_t d, int nq)
+decode_kernel(const float *__restrict__ M, float *__restrict__ g, const DecTerm *__restrict__ terms, int nterms, int64_t d, int nq,
+              float *__restrict__ w, float lr)
 {
     const int q = blockIdx.x * 256 + threadIdx.x;
     if (q >= nq) return;
@@ -670,6 +671,13 @@ decode_kernel(const float *__restrict__ M, float *__restrict__ g, const DecTerm 
 #pragma unroll
     for (int v = 0; v < VEC; ++v) out[v] = static_cast<float>(acc[v]);
     store_row<VEC>(g + col, out);
+    if (w) {
+        // the gradient step of the same columns, from the rounded g that was just stored; a column shared with the neighbouring
+        // chunk is stepped by the chunk that owns it only
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+            if (chunk_owns<VEC>(q, v, nq, static_cast<int>(d))) w[col + v] = fmaf(-lr, out[v], w[col + v]);
+    }
 }
 
 __global__ void __launch_bounds__(256) update_kernel(float *__restrict__ w, const float *__restrict__ g, float lr, int64_t d)
@@ -902,14 +910,14 @@ hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int n
     return launch_encode_shape<1, 1, 256, 8, double>(G, M, prog, num_sub, L, d, stream);
 }
 
-hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, hipStream_t stream)
+hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, float *w, float lr, hipStream_t stream)
 {
     if (d >= 4) {
         const int nq = static_cast<int>((d + 3) / 4);
-        decode_kernel<4><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq);
+        decode_kernel<4><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq, w, lr);
     } else {
         const int nq = static_cast<int>(d);
-        decode_kernel<1><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq);
+        decode_kernel<1><<<(nq + 255) / 256, 256, 0, stream>>>(M, g, terms, nterms, d, nq, w, lr);
     }
     return hipGetLastError();
 }
