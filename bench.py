@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E bandwidth
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X, published (packed fp32); 78.6 without packed instructions
 KERNEL_NAMES = ["partial_grads", "reduce_pieces", "encode", "decode", "update"]
 DESCRIPTIONS = {
     "cfg1": "CR tree L=2 n=3 s=1, linear regression fp32, m=1200 d=100",
@@ -211,6 +212,15 @@ def main() -> int:
     if roofline["traffic"]:
         # what HBM really moved (rocprofv3 counters of an earlier run of this workload), as a rate over this run's kernel time
         roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9
+    if not aggregate and cfg["x_dtype"] == wl.BF16:
+        # bf16 rows: stage 1 is bound by vector-ALU issue (a widening operation and two multiply-adds per element), not by memory;
+        # 4 flop per element of X visited against the chip's fp32 vector peak (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop,
+        # x 2 with packed instructions, which this build does not use)
+        flops = 4.0 * info.row_visits * d
+        achieved = flops / (dk["avg_ms"] * 1e-3) / 1e12
+        roofline = dict(roofline, bound="alu", achieved=achieved, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / FP32_VECTOR_PEAK_TFLOPS, flops_per_launch=flops,
+                        hbm_view={"achieved_GBps": dk["algorithmic_GBps"], "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS})
 
     # ---- CPU baseline: the oracle on the host cores, same inputs, bounded; also a parity check of one more GPU iteration
     baseline, parity = None, None
