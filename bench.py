@@ -209,9 +209,15 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["algorithmic_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS, "traffic": load_traffic(args.workload),
                 "avg_kernel_ms": dk["avg_ms"], "algorithmic_bytes_per_launch": dk["algorithmic_bytes_per_launch"]}
+    # yardstick: what a plain streaming read of the same buffer reaches on this device right now
+    big = G_dev if aggregate else X_dev
+    sink = torch.empty(16384, dtype=torch.float32, device="cuda")
+    nbytes = min(big.numel() * big.element_size(), 4 << 30) // 16 * 16
+    roofline["stream_read_GBps"] = cr.cr_probe_read_bandwidth(big, nbytes, sink, 10, torch.cuda.current_stream().cuda_stream)
     if roofline["traffic"]:
         # what HBM really moved (rocprofv3 counters of an earlier run of this workload), as a rate over this run's kernel time
         roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9
+        roofline["traffic_frac_of_stream_read"] = roofline["traffic_GBps"] / roofline["stream_read_GBps"]
     if not aggregate and cfg["x_dtype"] == wl.BF16:
         # bf16 rows: stage 1 is bound by vector-ALU issue (a widening operation and two multiply-adds per element), not by memory;
         # 4 flop per element of X visited against the chip's fp32 vector peak (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop,

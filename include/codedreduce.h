@@ -191,6 +191,12 @@ int cr_profile_read(cr_plan_t *plan, int kernel, double *total_ms, int64_t *laun
 /* algorithmic bytes of the most recent launch of a kernel id (0 if none yet) */
 int cr_last_algorithmic_bytes(const cr_plan_t *plan, int kernel, int64_t *bytes);
 int cr_synchronize(cr_plan_t *plan); /* wait for the bound stream */
+/* What a plain streaming read reaches on this device: `launches` launches of a kernel that only reads src_dev[0 .. bytes) with
+ * 16-byte loads (every workgroup sums what it reads into sink_dev so that nothing is optimised away), timed with HIP events on the
+ * given stream; the call waits for them.  A yardstick for the traffic figures of the hot path, not part of it.
+ *   src_dev   device, 16-byte aligned, bytes a multiple of 16 and at least 1 MiB;  sink_dev  device, at least 16384 floats
+ *   gbps      receives bytes * launches / elapsed in GB/s (the first launch is a warm-up and not timed) */
+int cr_probe_read_bandwidth(const void *src_dev, size_t bytes, float *sink_dev, int launches, void *hip_stream, double *gbps);
 
 const char *cr_last_error(void);
 

@@ -28,6 +28,7 @@ EXPORTS = [
     "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
+    "cr_probe_read_bandwidth",
 ]
 
 
@@ -84,6 +85,7 @@ def load_library():
         lib.cr_profile_read.argtypes = [vp, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         lib.cr_last_algorithmic_bytes.argtypes = [vp, c_int, ctypes.POINTER(i64)]
         lib.cr_synchronize.argtypes = [vp]
+        lib.cr_probe_read_bandwidth.argtypes = [vp, ctypes.c_size_t, vp, c_int, vp, ctypes.POINTER(ctypes.c_double)]
         _lib = lib
     return _lib
 
@@ -263,6 +265,13 @@ def cr_last_algorithmic_bytes(plan: int, kernel: int) -> int:
 
 def cr_synchronize(plan: int) -> None:
     _check(load_library().cr_synchronize(plan))
+
+
+def cr_probe_read_bandwidth(src, nbytes: int, sink, launches: int = 10, stream: int = 0) -> float:
+    """GB/s of a plain streaming read of src[0:nbytes] (device buffers; sink holds at least 16384 floats)."""
+    gbps = ctypes.c_double()
+    _check(load_library().cr_probe_read_bandwidth(_ptr(src), nbytes, _ptr(sink), launches, stream, ctypes.byref(gbps)))
+    return gbps.value
 
 
 # ---- memory plumbing (torch owns device memory and the stream) ------------------------------------------------------

@@ -806,6 +806,30 @@ int cr_profile_read(cr_plan_t *p, int kernel, double *total_ms, int64_t *launche
     return CR_OK;
 }
 
+int cr_probe_read_bandwidth(const void *src, size_t bytes, float *sink, int launches, void *hip_stream, double *gbps)
+{
+    if (!src || !sink || !gbps) return fail(CR_E_INVAL, "NULL argument");
+    if (bytes < (size_t(1) << 20) || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+        return fail(CR_E_INVAL, "src must be 16-byte aligned, bytes a multiple of 16 and at least 1 MiB");
+    if (launches < 1 || launches > 1000) return fail(CR_E_INVAL, "launches must be 1..1000");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t start = nullptr, stop = nullptr;
+    CR_HIP(hipEventCreate(&start));
+    if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(start); return fail(CR_E_HIP, "hipEventCreate failed"); }
+    hipError_t e = cr::launch_stream_read(src, bytes / 16, sink, stream);                 // warm-up
+    if (e == hipSuccess) e = hipEventRecord(start, stream);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) e = cr::launch_stream_read(src, bytes / 16, sink, stream);
+    if (e == hipSuccess) e = hipEventRecord(stop, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(stop);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, start, stop);
+    (void)hipEventDestroy(start);
+    (void)hipEventDestroy(stop);
+    if (e != hipSuccess) return fail(CR_E_HIP, std::string("read-bandwidth probe: ") + hipGetErrorString(e));
+    *gbps = static_cast<double>(bytes) * launches / (static_cast<double>(ms) * 1e-3) / 1e9;
+    return CR_OK;
+}
+
 int cr_last_algorithmic_bytes(const cr_plan_t *p, int kernel, int64_t *bytes)
 {
     if (!p || !bytes || kernel < 0 || kernel >= CR_K_COUNT) return fail(CR_E_INVAL, "bad argument");

@@ -74,6 +74,9 @@ hipError_t launch_encode(const float *G, float *M, const EncProgram &prog, int n
 // w != nullptr: also steps w <- w - lr g (g as stored, rounded to fp32) in the same launch
 hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nterms, int64_t d, float *w, float lr, hipStream_t stream);
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream);
+// plain streaming read of n16 16-byte words; every workgroup writes its sum to sink[workgroup] (kStreamGroups workgroups)
+constexpr int kStreamGroups = 256 * 8;
+hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStream_t stream);
 hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream);
 
 }  // namespace cr

@@ -922,6 +922,38 @@ hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nte
     return hipGetLastError();
 }
 
+// ---- yardstick: a plain streaming read ------------------------------------------------------------------------------------
+// Every thread walks the array with a stride of the whole grid, eight 16-byte loads in flight; nothing but the loads and one add
+// per word.  What this reaches is the practical ceiling for traffic that really comes from HBM.
+__global__ void __launch_bounds__(256) stream_read_kernel(const f4a *__restrict__ src, size_t n16, float *__restrict__ sink)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    float s = 0.f;
+    size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        f4a v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u].x + v[u].y + v[u].z + v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const f4a v = __builtin_nontemporal_load(src + i);
+        s += v.x + v.y + v.z + v.w;
+    }
+    s = wave_sum<true>(s);
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStream_t stream)
+{
+    stream_read_kernel<<<kStreamGroups, 256, 0, stream>>>(static_cast<const f4a *>(src), n16, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream)
 {
     update_kernel<<<static_cast<unsigned>((d + 255) / 256), 256, 0, stream>>>(w, g, lr, d);

@@ -437,3 +437,15 @@ def test_random_sweep_of_staged_kernels():
         _check_iteration(hip, orc, data["w0"], mask, TOL[cr.CR_F32])
         hip.close()
 
+
+def test_read_bandwidth_probe_reads_every_word():
+    torch = _torch()
+    n = (1 << 24) + 12                                    # floats; not a multiple of the probe's stride
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    sink = torch.zeros(16384, dtype=torch.float32, device="cuda")
+    gbps = cr.cr_probe_read_bandwidth(src, n * 4, sink, launches=3)
+    assert float(sink.double().sum()) == n               # every word was read exactly once in the last launch
+    assert gbps > 100.0
+    with pytest.raises(cr.CodedReduceError):
+        cr.cr_probe_read_bandwidth(src, 1024, sink)
+
