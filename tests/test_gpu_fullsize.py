@@ -137,6 +137,36 @@ def test_cfg5_full():
     hip.close()
 
 
+def test_four_holders_two_workgroups_per_unit_full():
+    """A (2,4,1) tree over 366 000 x 2 048 fp32 (3 GB): the staged kernel with four holders per workgroup and, rows being 8 KB,
+    two workgroups per compute unit."""
+    cfg = wl.config("cfg2", m=366_000, d=2_048, lr=3e-7)
+    data = wl.make_dataset(cfg, threads=16)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, use_native=True)
+    assert (hip.info.split_kind, hip.info.stage1_staged, hip.info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, 1, 4)
+    assert 256 * 4 < hip.info.num_teams <= 512 * 4         # more than one workgroup per unit
+    _full_first_step(hip, orc, data["w0"], wl.draw_mask(wl.mask_stream(cfg), 2, 4, 1), 1e-4)
+    _, ner = _gd_steps(hip, orc, cfg, data, 6, {0, 1, 5}, 1e-4)
+    assert all(b < a for a, b in zip(ner, ner[1:]))
+    hip.close()
+
+
+def test_gradient_coding_twenty_workers_full():
+    """One layer, 20 workers, 4 stragglers tolerated, on configuration 2's data: five holders per row, so three workgroups of two
+    holders per cell, side by side in gangs of three."""
+    cfg = wl.config("gc20")
+    data = wl.make_dataset(cfg, threads=16)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, use_native=True)
+    assert (hip.info.split_kind, hip.info.stage1_staged, hip.info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, 1, 2)
+    assert hip.info.row_visits == 5 * cfg["m"]
+    _full_first_step(hip, orc, data["w0"], wl.draw_mask(wl.mask_stream(cfg), 1, 20, 4), 1e-4)
+    _, ner = _gd_steps(hip, orc, cfg, data, 4, {0, 3}, 1e-4)
+    assert all(b < a for a, b in zip(ner, ner[1:]))
+    hip.close()
+
+
 def test_cfg4_full():
     """Aggregation only: L=2, n=8, s=2 (72 workers), 248 partition-gradient vectors of length 2^24, 20 random masks."""
     torch = _torch()
