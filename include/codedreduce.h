@@ -146,8 +146,10 @@ int cr_bind_workspace(cr_plan_t *plan, void *dev_ptr, size_t bytes, void *hip_st
 /* ---- the hot path ------------------------------------------------------------------------------------------------
  * cr_partial_grads (CR.Execute step 1): for every slab p,  G[p] = X[b:e]^T (phi(X[b:e] w) - y[b:e]),  phi = identity or sigmoid.
  *   X_dev  m x d row-major, contiguous, fp32 or bf16 per the plan, 16-byte aligned;  y_dev m floats;  w_dev d floats.
- *   Every holder of a row reads it itself (the redundancy is the method); X is read once per holder as long as a row fits the
- *   registers of one team (d <= 24576, whether or not d is a multiple of the 16-byte chunk); wider rows take two passes.
+ *   Every holder of a row does all of its own arithmetic on it (the redundancy is the method) in one pass over its rows, as long
+ *   as a row fits the registers of one team (d <= 24576, whether or not d is a multiple of the 16-byte chunk); wider rows take
+ *   two passes.  Holders of the same rows are scheduled together, so that one fetch from HBM serves them all: through the L2
+ *   (row cells) or, with shared cells, once per workgroup through LDS (see cr_plan_set_split).
  * cr_load_partial_grads: use caller-supplied slab gradients G_dev[S][d] (fp32, 16-byte aligned) in place of stage 1;
  *   the buffer is read in place by cr_encode_tree and must stay valid until then.
  * cr_encode_tree (CR.Execute steps 2-5): mask is HOST memory, N bytes, non-zero = straggler.  For every non-straggler node,
