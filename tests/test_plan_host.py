@@ -275,6 +275,17 @@ def test_argument_errors(plans):
     assert lib.cr_partial_grads(p, 16, 16, 16) == cr.CR_E_INVAL and "workspace" in cr.cr_last_error()
     assert lib.cr_encode_tree(p, 16) == cr.CR_E_INVAL
     assert lib.cr_plan_info(None, None) == cr.CR_E_INVAL
+    # timing: the kernel selection is a mask over the five kernel ids
+    assert lib.cr_profile_enable(p, cr.CR_PROFILE_ALL + 1) == cr.CR_E_INVAL and lib.cr_profile_enable(p, -1) == cr.CR_E_INVAL
+    assert lib.cr_profile_enable(p, 1 << cr.CR_K_ENCODE) == cr.CR_OK and lib.cr_profile_enable(p, 0) == cr.CR_OK
+    assert cr.cr_profile_read(p, cr.CR_K_ENCODE) == (0.0, 0, 0)
+    # the read-bandwidth yardstick checks its arguments before it touches the device
+    import ctypes
+    gbps = ctypes.c_double()
+    assert lib.cr_probe_read_bandwidth(None, 1 << 20, 16, 1, None, ctypes.byref(gbps)) == cr.CR_E_INVAL
+    assert lib.cr_probe_read_bandwidth(16, 1 << 10, 16, 1, None, ctypes.byref(gbps)) == cr.CR_E_INVAL        # under 1 MiB
+    assert lib.cr_probe_read_bandwidth(16, (1 << 20) + 8, 16, 1, None, ctypes.byref(gbps)) == cr.CR_E_INVAL  # not a multiple of 16
+    assert lib.cr_probe_read_bandwidth(16, 1 << 20, 16, 0, None, ctypes.byref(gbps)) == cr.CR_E_INVAL
 
 
 def test_random_trees_against_the_oracle(plans):
