@@ -136,7 +136,7 @@ def main() -> int:
     # ---- inputs, generated on the host from the seed and moved to HBM before any timing
     data = None
     if aggregate:
-        node, rb, re_, coef = cr.cr_plan_get_slabs(plan)
+        rb, re_, coef, node = cr.cr_plan_get_segments(plan)
         cuts, member = wl.atoms_of(rb, re_)
         atoms_dev = torch.empty((len(cuts) - 1, d), dtype=torch.float32, device="cuda")
         step_cols = 1 << 22

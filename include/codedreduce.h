@@ -76,8 +76,18 @@ typedef struct cr_plan_info {
     int64_t row_visits;      /* sum over workers of allocated rows */
     int64_t min_rows, max_rows; /* smallest / largest per-worker load; both equal r_CR m up to integer cuts (Theorem 1) */
     int64_t split_value;     /* teams (equal ranges) or rows per cell (row cells, shared cells); 0 until the split is known */
-    double gamma;            /* max_f sum_i |a_fi| ||b_i||_2 / sqrt(n): rounding amplification of one decode */
+    double gamma;            /* max_f sum_i |a_fi| ||b_i||_2 / sqrt(n): rounding amplification of one decode.  Messages are fp32, so
+                              * a decoded gradient carries a relative rounding error of about gamma^L * 2^-24 (see code_warning) */
     double r_cr;             /* computation load of Theorem 1 */
+    int32_t l2_domains;      /* L2 cache domains (accelerator dies) the stage-1 split was laid out for: queried from the device when
+                              * the split is fixed, 8 (MI355X) without a device */
+    int32_t unit_slots;      /* workgroup slots (compute units, or twice that for short rows) of the shared-cells split; 0 otherwise */
+    int32_t l2_sharing;      /* do workgroups whose ids are congruent modulo l2_domains run on the same die, as the row-cell and
+                              * shared-cell splits assume?  1: checked on the device at cr_bind_workspace; 0: checked and NOT so
+                              * (results stay exact, but every holder of a row then fetches it from HBM itself); -1: not checked
+                              * (no workspace bound yet, or the split does not rely on it) */
+    int32_t code_warning;    /* 1 if gamma^L * 2^-24 exceeds 1e-5, a tenth of the fp32 parity bar: the code is too badly
+                              * conditioned for fp32 messages to be trusted to 1e-4 (wide groups with s+1 not dividing n) */
 } cr_plan_info_t;
 
 /* ---- plan (host only; Section III-A CR.Allocate, Algorithms 1 and 2, Section II-C for the code) ------------
@@ -90,7 +100,7 @@ typedef struct cr_plan_info {
  *   seed         seeds the counter-based search for a well-conditioned code (ignored when B is given)
  *   B_or_null    host, n*n doubles row-major: use this encoding matrix (s+1 non-zeros in every row and column); or NULL
  *   out          receives the plan; destroy with cr_plan_destroy
- * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, d>2^28, m<N, m>2^40, C(n,s) > 2^20, N > 2^24, an unsupported B. */
+ * Errors: CR_E_INVAL for L<1, L>8, n<2, n>64, s<0, s>=n, d<1, d>2^28 (any model), m<N, m>2^40, C(n,s) > 2^20, N > 2^24, an unsupported B. */
 int cr_plan(int L, int n, int s, int64_t m, int64_t d, cr_plan_t **out);
 int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype, uint64_t seed,
                const double *B_or_null, cr_plan_t **out);
@@ -100,8 +110,10 @@ void cr_plan_destroy(cr_plan_t *plan);
 int cr_plan_info(const cr_plan_t *plan, cr_plan_info_t *info);
 int cr_plan_get_B(const cr_plan_t *plan, double *B /* host, n*n */);
 int cr_plan_get_A(const cr_plan_t *plan, double *A /* host, F*n, row f = f-th straggler set in lexicographic order */);
-/* slab p: worker node[p] holds rows [row_begin[p], row_end[p]) of X with combining coefficient coef[p]; arrays of S entries, any may be NULL */
-int cr_plan_get_slabs(const cr_plan_t *plan, int32_t *node, int64_t *row_begin, int64_t *row_end, double *coef);
+/* The allocation (CR.Allocate, Algorithm 2): segment p = rows [row_begin[p], row_end[p]) of X, held by worker[p] with combining
+ * coefficient coef[p]; segments are listed worker-major, in allocation order; each owns one slab (a d-float partial gradient), so
+ * there are S = num_slabs of them.  Arrays of S entries, any may be NULL. */
+int cr_plan_get_segments(const cr_plan_t *plan, int64_t *row_begin, int64_t *row_end, double *coef, int32_t *worker);
 /* decode row for one sibling group (Section III-A, CR.Execute step 3): flags[j] != 0 marks child j a straggler.  With fewer than
  * s stragglers the set is padded with the highest-index survivors.  a: host, n doubles.  CR_E_UNDECODABLE if more than s are set. */
 int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */, double *a);
@@ -156,7 +168,8 @@ int cr_bind_workspace(cr_plan_t *plan, void *dev_ptr, size_t bytes, void *hip_st
  *   m_(l,i) = sum_p coef_p G[p] over its slabs  +  sum_j a_j m_(l+1, n i + j)  with a = the decode row of its children group.
  *   Stragglers write no message (their row of M keeps stale data); all other nodes do, also below a straggler.
  *   CR_E_UNDECODABLE, before anything is enqueued and with no state change, if any group has more than s stragglers.
- * cr_decode_root: g_dev[d] = sum_j a_j m_(1,j) with the decode row of group 0 from the last cr_encode_tree.
+ * cr_decode_root (the last step of CR.Execute, Algorithm 2: the master recovers g from any n-s of its children):
+ *   g_dev[d] = sum_j a_j m_(1,j) with the decode row of group 0 from the last cr_encode_tree; by eq. (3) this is the full gradient.
  * cr_gd_update: w <- w - lr * g (plain gradient step used by the benchmark loop).
  * Errors: CR_E_STATE out of order; CR_E_INVAL unbound workspace / NULL / misaligned pointers; CR_E_HIP launch failures. */
 int cr_partial_grads(cr_plan_t *plan, const void *X_dev, const float *y_dev, const float *w_dev);
@@ -180,7 +193,7 @@ int cr_gd_run(cr_plan_t *plan, const void *X_dev, const float *y_dev, float *w_d
 int cr_get_slab_grads(const cr_plan_t *plan, const float **G_dev); /* S x d */
 int cr_get_messages(const cr_plan_t *plan, const float **M_dev);   /* N x d, row = worker id */
 
-/* ---- timing ---------------------------------------------------------------------------------------------------------
+/* ==== instrumentation: measurement plumbing for benchmarks and tests; no step of the method needs any of it ================
  * cr_profile_enable(plan, kernels): bit k of `kernels` set = every launch of kernel id k is bracketed by two HIP events on the
  * bound stream from now on (CR_PROFILE_ALL: all of them, 0: none); a non-zero call also clears the totals.  Each bracket costs
  * a few microseconds of device time, which shows on small problems.  cr_profile_read waits for the stream, then returns for one

@@ -24,7 +24,7 @@ CR_SPLIT_EQUAL_RANGES, CR_SPLIT_ROW_CELLS, CR_SPLIT_SHARED_CELLS = 0, 1, 2
 DEFAULT_SEED = 190201981
 
 EXPORTS = [
-    "cr_plan", "cr_plan_ex", "cr_plan_destroy", "cr_plan_info", "cr_plan_get_B", "cr_plan_get_A", "cr_plan_get_slabs",
+    "cr_plan", "cr_plan_ex", "cr_plan_destroy", "cr_plan_info", "cr_plan_get_B", "cr_plan_get_A", "cr_plan_get_segments",
     "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
@@ -43,7 +43,8 @@ class cr_plan_info_t(ctypes.Structure):
                                               "num_decode_rows", "code_candidate", "num_teams", "num_pieces", "split_kind",
                                               "stage1_team_size", "stage1_teams_per_group", "stage1_staged")] + \
                [(k, ctypes.c_int64) for k in ("m", "d", "row_visits", "min_rows", "max_rows", "split_value")] + \
-               [("gamma", ctypes.c_double), ("r_cr", ctypes.c_double)]
+               [("gamma", ctypes.c_double), ("r_cr", ctypes.c_double)] + \
+               [(k, ctypes.c_int32) for k in ("l2_domains", "unit_slots", "l2_sharing", "code_warning")]
 
 
 _lib = None
@@ -65,7 +66,7 @@ def load_library():
         lib.cr_plan_info.argtypes = [vp, ctypes.POINTER(cr_plan_info_t)]
         lib.cr_plan_get_B.argtypes = [vp, vp]
         lib.cr_plan_get_A.argtypes = [vp, vp]
-        lib.cr_plan_get_slabs.argtypes = [vp, vp, vp, vp, vp]
+        lib.cr_plan_get_segments.argtypes = [vp, vp, vp, vp, vp]
         lib.cr_plan_decode_row.argtypes = [vp, vp, vp]
         lib.cr_plan_set_split.argtypes = [vp, c_int, i64]
         lib.cr_plan_get_pieces.argtypes = [vp, vp, vp, vp, vp]
@@ -100,14 +101,44 @@ def _check(status: int) -> None:
 
 
 def _ptr(buf) -> int:
-    """Address of a torch tensor / numpy array, or an integer address passed through."""
+    """Address of a host numpy array, or an integer address passed through."""
     if buf is None:
         return 0
     if isinstance(buf, int):
         return buf
     if isinstance(buf, np.ndarray):
         return buf.ctypes.data
+    raise TypeError("expected a numpy array or an integer address")
+
+
+_TORCH_DTYPES = {"f32": ("torch.float32",), "x_f32": ("torch.float32",), "x_bf16": ("torch.bfloat16", "torch.int16", "torch.uint16")}
+
+
+def _dev(buf, name: str, kind: str, numel: int, optional: bool = False) -> int:
+    """Address of a device buffer for the argument `name`.  A torch tensor is checked (on the GPU, element type `kind`, contiguous,
+    at least `numel` elements): a wrong buffer must become a Python error here, not a memory fault in a kernel.  A plain integer is
+    taken to be a device address the caller vouches for."""
+    if buf is None:
+        if optional:
+            return 0
+        raise ValueError(f"{name} is required")
+    if isinstance(buf, int):
+        return buf
+    if isinstance(buf, np.ndarray):
+        raise ValueError(f"{name} must be a device buffer, not a host numpy array")
+    if not getattr(buf, "is_cuda", False):
+        raise ValueError(f"{name} must live on the GPU")
+    if str(buf.dtype) not in _TORCH_DTYPES[kind]:
+        raise ValueError(f"{name} has dtype {buf.dtype}, expected {_TORCH_DTYPES[kind][0]}")
+    if not buf.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if buf.numel() < numel:
+        raise ValueError(f"{name} has {buf.numel()} elements, the plan needs {numel}")
     return buf.data_ptr()
+
+
+def _x_kind(info) -> str:
+    return "x_bf16" if info.x_dtype == CR_BF16 else "x_f32"
 
 
 # ---- plan ------------------------------------------------------------------------------------------------------------
@@ -151,13 +182,14 @@ def cr_plan_get_A(plan: int) -> np.ndarray:
     return A
 
 
-def cr_plan_get_slabs(plan: int):
+def cr_plan_get_segments(plan: int):
+    """Returns (row_begin, row_end, coef, worker), S entries each."""
     S = cr_plan_info(plan).num_slabs
-    node = np.empty(S, dtype=np.int32)
+    worker = np.empty(S, dtype=np.int32)
     rb, re = np.empty(S, dtype=np.int64), np.empty(S, dtype=np.int64)
     coef = np.empty(S, dtype=np.float64)
-    _check(load_library().cr_plan_get_slabs(plan, node.ctypes.data, rb.ctypes.data, re.ctypes.data, coef.ctypes.data))
-    return node, rb, re, coef
+    _check(load_library().cr_plan_get_segments(plan, rb.ctypes.data, re.ctypes.data, coef.ctypes.data, worker.ctypes.data))
+    return rb, re, coef, worker
 
 
 def cr_plan_decode_row(plan: int, flags) -> np.ndarray:
@@ -200,15 +232,20 @@ def cr_workspace_bytes(plan: int) -> int:
 
 
 def cr_bind_workspace(plan: int, workspace, nbytes: int, stream: int = 0) -> None:
-    _check(load_library().cr_bind_workspace(plan, _ptr(workspace), nbytes, stream))
+    if not isinstance(workspace, int):
+        raise TypeError("workspace is a device address (see Workspace for a torch-owned block)")
+    _check(load_library().cr_bind_workspace(plan, workspace, nbytes, stream))
 
 
 def cr_partial_grads(plan: int, X, y, w) -> None:
-    _check(load_library().cr_partial_grads(plan, _ptr(X), _ptr(y), _ptr(w)))
+    info = cr_plan_info(plan)
+    _check(load_library().cr_partial_grads(plan, _dev(X, "X", _x_kind(info), info.m * info.d), _dev(y, "y", "f32", info.m),
+                                           _dev(w, "w", "f32", info.d)))
 
 
 def cr_load_partial_grads(plan: int, G) -> None:
-    _check(load_library().cr_load_partial_grads(plan, _ptr(G)))
+    info = cr_plan_info(plan)
+    _check(load_library().cr_load_partial_grads(plan, _dev(G, "G", "f32", info.num_slabs * info.d)))
 
 
 def cr_encode_tree(plan: int, straggler_mask) -> None:
@@ -219,18 +256,23 @@ def cr_encode_tree(plan: int, straggler_mask) -> None:
 
 
 def cr_decode_root(plan: int, g) -> None:
-    _check(load_library().cr_decode_root(plan, _ptr(g)))
+    _check(load_library().cr_decode_root(plan, _dev(g, "g", "f32", cr_plan_info(plan).d)))
 
 
 def cr_gd_update(plan: int, w, g, lr: float) -> None:
-    _check(load_library().cr_gd_update(plan, _ptr(w), _ptr(g), lr))
+    d = cr_plan_info(plan).d
+    _check(load_library().cr_gd_update(plan, _dev(w, "w", "f32", d), _dev(g, "g", "f32", d), lr))
 
 
 def cr_gd_run(plan: int, X, y, w, g, masks, lr: float, w_star=None, metrics=None) -> None:
     m = np.ascontiguousarray(masks, dtype=np.uint8)
     if m.ndim != 2 or m.shape[1] != cr_plan_info(plan).num_workers:
         raise ValueError("masks must be steps x N bytes")
-    _check(load_library().cr_gd_run(plan, _ptr(X), _ptr(y), _ptr(w), _ptr(g), m.ctypes.data, m.shape[0], lr, _ptr(w_star), _ptr(metrics)))
+    info = cr_plan_info(plan)
+    _check(load_library().cr_gd_run(plan, _dev(X, "X", _x_kind(info), info.m * info.d), _dev(y, "y", "f32", info.m),
+                                    _dev(w, "w", "f32", info.d), _dev(g, "g", "f32", info.d), m.ctypes.data, m.shape[0], lr,
+                                    _dev(w_star, "w_star", "f32", info.d, optional=True),
+                                    _dev(metrics, "metrics", "f32", 2 * m.shape[0], optional=True)))
 
 
 def cr_get_slab_grads(plan: int) -> int:
@@ -270,7 +312,12 @@ def cr_synchronize(plan: int) -> None:
 def cr_probe_read_bandwidth(src, nbytes: int, sink, launches: int = 10, stream: int = 0) -> float:
     """GB/s of a plain streaming read of src[0:nbytes] (device buffers; sink holds at least 16384 floats)."""
     gbps = ctypes.c_double()
-    _check(load_library().cr_probe_read_bandwidth(_ptr(src), nbytes, _ptr(sink), launches, stream, ctypes.byref(gbps)))
+    if not isinstance(src, int) and src.numel() * src.element_size() < nbytes:
+        raise ValueError("src is shorter than nbytes")
+    sp = src if isinstance(src, int) else (src.data_ptr() if getattr(src, "is_cuda", False) and src.is_contiguous() else None)
+    if sp is None:
+        raise ValueError("src must be a contiguous device buffer")
+    _check(load_library().cr_probe_read_bandwidth(sp, nbytes, _dev(sink, "sink", "f32", 16384), launches, stream, ctypes.byref(gbps)))
     return gbps.value
 
 

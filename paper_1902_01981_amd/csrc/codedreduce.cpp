@@ -70,6 +70,8 @@ struct cr_plan_s {
     int64_t split_value = 0;
     int split_kind_used = -1;                       // what ensure_split settled on
     int64_t split_value_used = 0;
+    int l2_domains = 0, unit_slots = 0;             // what the split was laid out for (0 until it is fixed)
+    int l2_sharing = -1;                            // 1 / 0: workgroup ids congruent modulo l2_domains were seen (not) to share a die; -1: not checked
     cr::Split split;
 
     // device binding
@@ -80,6 +82,7 @@ struct cr_plan_s {
     cr::DevPiece *d_pieces = nullptr;
     int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr, *d_slab_pieces = nullptr;
     int32_t *d_group_item_begin = nullptr, *d_item_pieces = nullptr;   // shared queues only
+    uint32_t *d_placement = nullptr;               // kPlacementSlots words: where the workgroups of a probe launch ran
     char *d_program = nullptr;                     // per-call encode program + root decode terms
     size_t program_bytes = 0;
     float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr, *d_residuals = nullptr;   // residuals: wide-row path only
@@ -127,18 +130,30 @@ int group_decode_row(const cr_plan_t *p, const uint8_t *flags, const double **ro
     return CR_OK;
 }
 
-// MI355X has 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin by workgroup id.
-constexpr int kL2Domains = 8;
+// MI355X has 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin by workgroup id.  The count
+// is asked of the current device; without one (planning on a host without a GPU) MI355X's 8 is assumed.  Whether congruent workgroup
+// ids really share a die is checked on the device when a workspace is bound (see check_l2_sharing).
+constexpr int kDefaultL2Domains = 8, kDefaultUnits = 256;
+constexpr int kPlacementSlots = 1024;
+
+int query_l2_domains()
+{
+    int dev = 0, xccs = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&xccs, hipDeviceAttributeNumberOfXccs, dev) == hipSuccess && xccs >= 1 && xccs <= 64)
+        return xccs;
+    (void)hipGetLastError();
+    return kDefaultL2Domains;
+}
 
 // Workgroup slots of a staged kernel: one per compute unit of the current device (a multiple of the L2 domains; MI355X's 256
 // without a device).  Rows of at most 8 KB get two per unit where registers and LDS let two workgroups stay resident: their steps
 // are short, and the second workgroup fills the gaps around the first one's barriers (measured +10 to +16 % at 2048 columns;
 // longer rows gain nothing).
-int unit_slots(const cr::Stage1Variant *v, int64_t row_bytes)
+int unit_slots(const cr::Stage1Variant *v, int64_t row_bytes, int domains)
 {
     int dev = 0, cus = 0, resident = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kL2Domains) {
-        int slots = cus / kL2Domains * kL2Domains;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= domains) {
+        int slots = cus / domains * domains;
         if (v && row_bytes <= 8192 && cr::prepare_stage1(*v) == hipSuccess &&
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, v->fn[0], v->block(), v->lds_bytes()) == hipSuccess && resident >= 2)
             slots *= 2;
@@ -146,7 +161,7 @@ int unit_slots(const cr::Stage1Variant *v, int64_t row_bytes)
         return slots;
     }
     (void)hipGetLastError();
-    return 256;
+    return kDefaultUnits / domains * domains;
 }
 
 int ensure_split(cr_plan_t *p)
@@ -155,6 +170,10 @@ int ensure_split(cr_plan_t *p)
     int kind = p->split_kind;
     int64_t value = p->split_value;
     p->variant = p->variant_regs;
+    const int domains = query_l2_domains();
+    p->l2_domains = domains;
+    p->unit_slots = 0;
+    p->l2_sharing = -1;
     if (kind < 0 && p->s == 0) {
         // no redundancy (every row has one holder): nothing to share, so one contiguous range per resident workgroup streams best
         int dev = 0, cus = 0, per_cu = 0;
@@ -174,13 +193,13 @@ int ensure_split(cr_plan_t *p)
         // shortest; ties go to the taller cell (fewer partial rows).
         kind = CR_SPLIT_SHARED_CELLS;
         const int tpb = p->variant_staged->teams_per_block();
-        const int slots = unit_slots(p->variant_staged, p->d * elem_size(p));
+        const int slots = unit_slots(p->variant_staged, p->d * elem_size(p), domains);
         value = 512;
         if (p->row_visits / tpb / 64 <= (int64_t(1) << 16)) {       // with longer queues than that the last round no longer matters
             int64_t best = -1;
             cr::Split trial;
             for (int64_t c = 64; c <= 1024; c += 8) {
-                cr::split_shared_queues(p->slabs, c, kL2Domains, tpb, slots / kL2Domains, trial);
+                cr::split_shared_queues(p->slabs, c, domains, tpb, slots / domains, trial);
                 if (best < 0 || trial.makespan <= best) { best = trial.makespan; value = c; }
             }
         }
@@ -204,7 +223,8 @@ int ensure_split(cr_plan_t *p)
     p->split_value_used = value;
     if (kind == CR_SPLIT_SHARED_CELLS) {
         if (p->row_visits / value + 2 * static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        cr::split_shared_queues(p->slabs, value, kL2Domains, teams_per_block, unit_slots(p->variant, p->d * elem_size(p)) / kL2Domains, p->split);
+        p->unit_slots = unit_slots(p->variant, p->d * elem_size(p), domains);
+        cr::split_shared_queues(p->slabs, value, domains, teams_per_block, p->unit_slots / domains, p->split);
         // what the staged kernel relies on: every piece of an item covers the same rows
         const cr::Split &sp = p->split;
         for (size_t it = 0; it * teams_per_block < sp.item_pieces.size(); ++it) {
@@ -222,7 +242,7 @@ int ensure_split(cr_plan_t *p)
         }
     } else if (kind == CR_SPLIT_ROW_CELLS) {
         if (p->row_visits / value + static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        cr::split_row_cells(p->slabs, value, kL2Domains, teams_per_block, p->split);
+        cr::split_row_cells(p->slabs, value, domains, teams_per_block, p->split);
         if (!p->variant) {                                  // the wide-row kernels index pieces directly: no empty teams
             cr::Split compact;
             cr::split_row_cells(p->slabs, value, 1, 1, compact);
@@ -257,6 +277,7 @@ void compute_layout(cr_plan_t *p, size_t *total)
     w = align_up(w + P * sizeof(int32_t), 256);
     w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
     w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
+    w = align_up(w + kPlacementSlots * sizeof(uint32_t), 256);
     w = align_up(w + p->program_bytes, 256);
     const size_t row = static_cast<size_t>(p->d) * sizeof(float);
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -315,6 +336,31 @@ int fold_timings(cr_plan_t *p)
     return CR_OK;
 }
 
+// The row-cell and shared-cell splits put the holders of a cell on workgroup ids that are congruent modulo the number of L2
+// domains, trusting that the dispatcher deals workgroups to the dies round-robin.  This runs a launch of kPlacementSlots small
+// workgroups that record the die they ran on and checks exactly that; the verdict is reported by cr_plan_info (l2_sharing).
+// A device that places workgroups differently still computes the same results, only without the shared fetches.
+int check_l2_sharing(cr_plan_t *p)
+{
+    std::vector<uint32_t> where(kPlacementSlots);
+    CR_HIP(cr::launch_placement_probe(p->d_placement, kPlacementSlots, p->stream));
+    CR_HIP(hipMemcpyAsync(where.data(), p->d_placement, kPlacementSlots * sizeof(uint32_t), hipMemcpyDeviceToHost, p->stream));
+    CR_HIP(hipStreamSynchronize(p->stream));
+    const int domains = p->l2_domains;
+    std::vector<int> die_of(domains, -1);
+    bool ok = true;
+    for (int g = 0; g < kPlacementSlots && ok; ++g) {
+        const int die = static_cast<int>(where[g] >> 16);
+        int &seen = die_of[g % domains];
+        if (seen < 0) seen = die;
+        ok = seen == die;
+    }
+    for (int a = 0; a < domains && ok; ++a)                  // and distinct residues on distinct dies
+        for (int b = a + 1; b < domains; ++b) ok = ok && die_of[a] != die_of[b];
+    p->l2_sharing = ok ? 1 : 0;
+    return CR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -334,6 +380,7 @@ int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype
     if (n < 2 || n > 64) return fail(CR_E_INVAL, "n must be in 2..64");
     if (s < 0 || s >= n) return fail(CR_E_INVAL, "s must be in 0..n-1");
     if (d < 1) return fail(CR_E_INVAL, "d must be positive");
+    if (d > (int64_t(1) << 28)) return fail(CR_E_INVAL, "d exceeds 2^28");     // every kernel indexes columns with 32-bit integers
     if (model < CR_LINEAR || model > CR_AGGREGATE_ONLY) return fail(CR_E_INVAL, "unknown model");
     if (x_dtype != CR_F32 && x_dtype != CR_BF16) return fail(CR_E_INVAL, "unknown x_dtype");
     if (cr::num_straggler_sets(n, s, int64_t(1) << 20) < 0) return fail(CR_E_INVAL, "C(n,s) exceeds 2^20 straggler patterns");
@@ -365,7 +412,6 @@ int cr_plan_ex(int L, int n, int s, int64_t m, int64_t d, int model, int x_dtype
             for (int l = 0; l < L && max_holders < 64; ++l) max_holders *= s + 1;
             p->variant_staged = s > 0 ? cr::select_stage1_staged(x_dtype, d, max_holders) : nullptr;   // nullptr: no such kernel for this width
             p->variant = p->variant_regs;
-            if (d > (int64_t(1) << 28)) { delete p; return fail(CR_E_INVAL, "d exceeds 2^28"); }
         }
     } catch (const std::bad_alloc &) {
         delete p;
@@ -412,6 +458,10 @@ int cr_plan_info(const cr_plan_t *p, cr_plan_info_t *info)
     double q = static_cast<double>(p->n) / (p->s + 1), sum = 0.0, pw = 1.0;
     for (int l = 1; l <= p->L; ++l) { pw *= q; sum += pw; }
     info->r_cr = 1.0 / sum;
+    info->l2_domains = p->l2_domains ? p->l2_domains : kDefaultL2Domains;
+    info->unit_slots = split_known ? p->unit_slots : 0;
+    info->l2_sharing = p->l2_sharing;
+    info->code_warning = std::pow(p->code.gamma, p->L) * std::ldexp(1.0, -24) > 1e-5 ? 1 : 0;
     return CR_OK;
 }
 
@@ -432,11 +482,11 @@ int cr_plan_get_A(const cr_plan_t *p, double *A)
     return CR_OK;
 }
 
-int cr_plan_get_slabs(const cr_plan_t *p, int32_t *node, int64_t *row_begin, int64_t *row_end, double *coef)
+int cr_plan_get_segments(const cr_plan_t *p, int64_t *row_begin, int64_t *row_end, double *coef, int32_t *worker)
 {
     if (!p) return fail(CR_E_INVAL, "NULL plan");
     for (size_t i = 0; i < p->slabs.size(); ++i) {
-        if (node) node[i] = p->slabs[i].node;
+        if (worker) worker[i] = p->slabs[i].node;
         if (row_begin) row_begin[i] = p->slabs[i].row_begin;
         if (row_end) row_end[i] = p->slabs[i].row_end;
         if (coef) coef[i] = p->slabs[i].coef;
@@ -532,6 +582,7 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     p->d_slab_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + P * sizeof(int32_t), 256);
     p->d_group_item_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
     p->d_item_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
+    p->d_placement = reinterpret_cast<uint32_t *>(p->ws + w);              w = align_up(w + kPlacementSlots * sizeof(uint32_t), 256);
     p->d_program = p->ws + w;                                              w = align_up(w + p->program_bytes, 256);
     p->d_partial = nullptr; p->d_G = nullptr;
     if (p->model != CR_AGGREGATE_ONLY) {
@@ -558,6 +609,11 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
             CR_HIP(hipMemcpy(p->d_group_item_begin, p->split.group_item_begin.data(), p->split.group_item_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice));
             CR_HIP(hipMemcpy(p->d_item_pieces, p->split.item_pieces.data(), p->split.item_pieces.size() * sizeof(int32_t), hipMemcpyHostToDevice));
         }
+    }
+    p->l2_sharing = -1;
+    if (P > 0 && (p->split_kind_used == CR_SPLIT_ROW_CELLS || p->split_kind_used == CR_SPLIT_SHARED_CELLS)) {
+        int rc = check_l2_sharing(p);
+        if (rc != CR_OK) return rc;
     }
     if (!p->h_staging) {
         CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kStagingSlots, hipHostMallocDefault));

@@ -77,6 +77,8 @@ hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStrea
 // plain streaming read of n16 16-byte words; every workgroup writes its sum to sink[workgroup] (kStreamGroups workgroups)
 constexpr int kStreamGroups = 256 * 8;
 hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStream_t stream);
+// one wavefront per workgroup; out[workgroup id] = (die the workgroup ran on) << 16 | (shader engine and compute unit inside the die)
+hipError_t launch_placement_probe(uint32_t *out, int groups, hipStream_t stream);
 hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream);
 
 }  // namespace cr

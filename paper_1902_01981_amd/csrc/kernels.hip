@@ -954,6 +954,20 @@ hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStrea
     return hipGetLastError();
 }
 
+// ---- where do workgroups run? -----------------------------------------------------------------------------------------
+// __smid() packs the hardware ids of the wave: die (XCC) above 6 bits of shader engine and compute unit.
+__global__ void __launch_bounds__(64) placement_probe_kernel(uint32_t *__restrict__ out)
+{
+    const unsigned id = __smid();
+    if (threadIdx.x == 0) out[blockIdx.x] = ((id >> 6) << 16) | (id & 63u);
+}
+
+hipError_t launch_placement_probe(uint32_t *out, int groups, hipStream_t stream)
+{
+    placement_probe_kernel<<<groups, 64, 0, stream>>>(out);
+    return hipGetLastError();
+}
+
 hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStream_t stream)
 {
     update_kernel<<<static_cast<unsigned>((d + 255) / 256), 256, 0, stream>>>(w, g, lr, d);

@@ -62,7 +62,7 @@ def test_allocation_matches_the_oracle(plans, L, n, s, m, d):
     p = plans(L, n, s, m, d, model=model)
     own, _ = cr_tree.cr_allocate(L, n, s, m, gc_code.design_code(n, s, L, cr.DEFAULT_SEED)[0])
     expect = cr_tree.slabs_of(own)
-    node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+    rb, re_, coef, node = cr.cr_plan_get_segments(p)
     assert len(expect) == len(node)
     assert [e[0] for e in expect] == list(node) and [e[1] for e in expect] == list(rb) and [e[2] for e in expect] == list(re_)
     np.testing.assert_allclose(coef, [e[3] for e in expect], rtol=1e-11, atol=1e-13)
@@ -93,7 +93,7 @@ def test_fall_back_to_fractional_repetition(plans, L, n, s):
     else:
         assert gamma ** L <= 256 or n % (s + 1) != 0
     own, _ = cr_tree.cr_allocate(L, n, s, info.m, Bo)     # allocation follows whichever code was chosen
-    node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+    rb, re_, coef, node = cr.cr_plan_get_segments(p)
     expect = cr_tree.slabs_of(own)
     assert [e[:3] for e in expect] == list(zip(node.tolist(), rb.tolist(), re_.tolist()))
     np.testing.assert_allclose(coef, [e[3] for e in expect], rtol=1e-11)
@@ -106,7 +106,7 @@ def test_printed_example_through_the_plan(plans, golden_dir):
     assert cr.cr_plan_info(p).code_candidate == -1
     assert np.array_equal(cr.cr_plan_get_B(p), np.array(ex["B"], dtype=float))
     np.testing.assert_allclose(cr.cr_plan_get_A(p), np.array(ex["A"], dtype=float), atol=1e-14)
-    node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+    rb, re_, coef, node = cr.cr_plan_get_segments(p)
     for nid, segs in ex["own_rows_m15"].items():
         if nid == "comment":
             continue
@@ -134,7 +134,7 @@ def test_decode_row_rule(plans):
 def test_work_split_covers_every_row_visit_once(plans, teams):
     p = plans(2, 4, 1, 10_007, 64)
     cr.cr_plan_set_split(p, cr.CR_SPLIT_EQUAL_RANGES, teams)
-    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    rb, re_, _, node = cr.cr_plan_get_segments(p)
     slab, pb, pe, team = cr.cr_plan_get_pieces(p)
     info = cr.cr_plan_info(p)
     assert info.num_teams == teams and info.num_pieces == len(slab)
@@ -150,7 +150,7 @@ def test_work_split_covers_every_row_visit_once(plans, teams):
 def test_row_cell_split(plans, cell_rows):
     p = plans(2, 4, 1, 10_007, 64)
     cr.cr_plan_set_split(p, cr.CR_SPLIT_ROW_CELLS, cell_rows)
-    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    rb, re_, _, node = cr.cr_plan_get_segments(p)
     slab, pb, pe, team = cr.cr_plan_get_pieces(p)
     info = cr.cr_plan_info(p)
     assert info.num_pieces == len(slab) <= info.num_teams and np.all(np.diff(team) > 0)   # at most one piece per team
@@ -174,7 +174,7 @@ def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
     neighbouring workgroups of one L2 domain, per_group of them per workgroup, and hold exactly the same rows."""
     p = plans(L, n, s, m, d)
     cr.cr_plan_set_split(p, cr.CR_SPLIT_SHARED_CELLS, cell_rows)
-    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    rb, re_, _, node = cr.cr_plan_get_segments(p)
     slab, pb, pe, team = cr.cr_plan_get_pieces(p)
     info = cr.cr_plan_info(p)
     assert info.num_pieces == len(slab) and info.num_teams <= 256 * per_group and np.all(np.diff(team) >= 0)
@@ -223,7 +223,7 @@ def test_run_time_model_matches_the_oracle(plans, L, n, s, m):
     from oracle import latency
 
     p = plans(L, n, s, m, 8)
-    node, rb, re_, _ = cr.cr_plan_get_slabs(p)
+    rb, re_, _, node = cr.cr_plan_get_segments(p)
     rows = np.bincount(node, weights=(re_ - rb), minlength=cr.cr_plan_info(p).num_workers).astype(np.int64)
     a, mu, t_c = 5e-5, 2e4, 0.05                          # the constants of the paper's simulated network experiment
     for it in [0, 1, 7, 1000]:
@@ -260,11 +260,17 @@ def test_holders_of_a_cell_share_an_l2_domain(plans, d, x_dtype, teams_per_group
 
 def test_argument_errors(plans):
     bad = [(0, 3, 1, 100, 4), (9, 2, 1, 10_000, 4), (2, 1, 0, 100, 4), (2, 65, 1, 10 ** 6, 4), (2, 3, 3, 100, 4), (2, 3, -1, 100, 4),
-           (2, 3, 1, 11, 4), (2, 3, 1, 100, 0), (2, 40, 20, 10 ** 6, 4)]
+           (2, 3, 1, 11, 4), (2, 3, 1, 100, 0), (2, 40, 20, 10 ** 6, 4), (2, 3, 1, 100, (1 << 28) + 1)]
     for args in bad:
         with pytest.raises(cr.CodedReduceError) as ei:
             plans(*args)
         assert ei.value.status == cr.CR_E_INVAL, args
+    # the column bound holds for every model: the kernels index columns with 32-bit integers, also without a data matrix
+    for d in ((1 << 28) + 4, (1 << 31) + 8):
+        with pytest.raises(cr.CodedReduceError) as ei:
+            plans(1, 4, 1, 1000, d, model=cr.CR_AGGREGATE_ONLY)
+        assert ei.value.status == cr.CR_E_INVAL
+    assert cr.cr_plan_info(plans(1, 4, 1, 1000, 1 << 28, model=cr.CR_AGGREGATE_ONLY)).d == 1 << 28
     with pytest.raises(cr.CodedReduceError):
         plans(2, 3, 1, 100, 4, B=np.eye(3))             # one partition per worker cannot survive a straggler
     p_wide = plans(2, 3, 1, 100, 30_000)                # rows too wide for the single-pass kernel: still planned (two-pass path)
@@ -305,7 +311,7 @@ def test_random_trees_against_the_oracle(plans):
         B = cr.cr_plan_get_B(p)
         np.testing.assert_allclose(B, Bo, atol=1e-11)
         own, _ = cr_tree.cr_allocate(L, n, s, m, Bo)
-        node, rb, re_, coef = cr.cr_plan_get_slabs(p)
+        rb, re_, coef, node = cr.cr_plan_get_segments(p)
         expect = cr_tree.slabs_of(own)
         assert [e[:3] for e in expect] == list(zip(node.tolist(), rb.tolist(), re_.tolist())), (L, n, s, m)
         np.testing.assert_allclose(coef, [e[3] for e in expect], rtol=1e-10, atol=1e-13)
@@ -322,3 +328,73 @@ def test_random_trees_against_the_oracle(plans):
         np.add.at(cover, slab, pe - pb)
         assert np.array_equal(cover, re_ - rb)               # every slab is tiled exactly
         assert np.all(pb >= rb[slab]) and np.all(pe <= re_[slab])
+
+
+def test_plan_reports_layout_assumptions_and_badly_conditioned_codes(plans):
+    """Without a device the split is laid out for MI355X (8 L2 domains, 256 units); the sharing check has not run.  A code whose
+    rounding amplification gamma^L * 2^-24 exceeds a tenth of the fp32 parity bar is flagged."""
+    p = plans(2, 4, 1, 100_000, 10_000)
+    cr.cr_plan_set_split(p, cr.CR_SPLIT_SHARED_CELLS, 368)
+    info = cr.cr_plan_info(p)
+    assert (info.l2_domains, info.unit_slots, info.l2_sharing, info.code_warning) == (8, 256, -1, 0)
+    assert info.num_teams <= info.unit_slots * info.stage1_teams_per_group
+    q = plans(2, 4, 1, 100_000, 10_000)
+    cr.cr_plan_set_split(q, cr.CR_SPLIT_EQUAL_RANGES, 100)
+    assert cr.cr_plan_info(q).unit_slots == 0
+    # one layer, 20 workers, 5 stragglers: s+1 does not divide n, so the cyclic code stays, with gamma in the 10^5
+    bad = cr.cr_plan_info(plans(1, 20, 5, 2_000, 16))
+    assert bad.code_candidate >= 0 and bad.gamma * 2.0 ** -24 > 1e-5 and bad.code_warning == 1
+    for L, n, s in [(2, 3, 1), (2, 4, 1), (3, 4, 1), (2, 8, 2), (3, 6, 2), (2, 12, 5), (2, 12, 3)]:
+        assert cr.cr_plan_info(plans(L, n, s, 40 * cr_tree.num_workers(n, L), 16)).code_warning == 0
+
+
+def test_binding_rejects_wrong_device_buffers(plans):
+    """A host array, a wrong element type, a short or strided buffer must be a Python error, never a kernel's memory fault."""
+    import torch
+
+    p = plans(2, 3, 1, 1200, 100)
+    X = np.zeros((1200, 100), dtype=np.float32)
+    y = np.zeros(1200, dtype=np.float32)
+    w = np.zeros(100, dtype=np.float32)
+    with pytest.raises(ValueError, match="host numpy"):
+        cr.cr_partial_grads(p, X, y, w)
+    with pytest.raises(ValueError, match="GPU"):
+        cr.cr_partial_grads(p, torch.from_numpy(X), torch.from_numpy(y), torch.from_numpy(w))
+    with pytest.raises(ValueError, match="GPU"):
+        cr.cr_decode_root(p, torch.zeros(100))
+    with pytest.raises(ValueError, match="GPU"):
+        cr.cr_gd_update(p, torch.zeros(100), torch.zeros(100), 0.1)
+    with pytest.raises(ValueError, match="required"):
+        cr.cr_decode_root(p, None)
+
+    class FakeDeviceTensor:                              # stands in for a CUDA tensor on a host without one
+        is_cuda = True
+
+        def __init__(self, dtype, numel, contiguous=True):
+            self.dtype, self._numel, self._c = dtype, numel, contiguous
+
+        def numel(self):
+            return self._numel
+
+        def is_contiguous(self):
+            return self._c
+
+        def data_ptr(self):
+            raise AssertionError("a rejected buffer must not reach the library")
+
+    with pytest.raises(ValueError, match="dtype"):
+        cr.cr_decode_root(p, FakeDeviceTensor(torch.float64, 100))
+    with pytest.raises(ValueError, match="elements"):
+        cr.cr_decode_root(p, FakeDeviceTensor(torch.float32, 99))
+    with pytest.raises(ValueError, match="contiguous"):
+        cr.cr_decode_root(p, FakeDeviceTensor(torch.float32, 100, contiguous=False))
+    with pytest.raises(ValueError, match="elements"):
+        cr.cr_load_partial_grads(p, FakeDeviceTensor(torch.float32, 27 * 100 - 1))
+    masks = np.zeros((3, 12), dtype=np.uint8)
+    ok = lambda n: type("T", (FakeDeviceTensor,), {"data_ptr": lambda self: 256})(torch.float32, n)
+    with pytest.raises(ValueError, match="metrics"):
+        cr.cr_gd_run(p, ok(120_000), ok(1200), ok(100), ok(100), masks, 0.1, None, FakeDeviceTensor(torch.float32, 5))
+    with pytest.raises(ValueError, match="X has dtype"):
+        cr.cr_gd_run(p, FakeDeviceTensor(torch.bfloat16, 120_000), ok(1200), ok(100), ok(100), masks, 0.1)
+    with pytest.raises(TypeError):
+        cr.cr_bind_workspace(p, np.zeros(16), 16)
