@@ -14,7 +14,7 @@ import pytest
 
 import paper_1902_01981_amd as cr
 from cr_inputs import workloads as wl
-from _harness import TOL, HipPath, OraclePath, rel_l2
+from _harness import TOL, WORST, HipPath, OraclePath, assert_close, gate_for, rel_l2
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -34,13 +34,15 @@ def _full_first_step(hip, orc, w, mask, tol):
     msgs, g_cr = orc.execute(orc.node_grads(sg), mask)
     gstar = orc.full_gradient(w)
     assert rel_l2(g_cr, gstar) < 1e-9
-    assert rel_l2(g, gstar) <= tol, rel_l2(g, gstar)
+    gate = gate_for(hip.info.gamma, hip.info.L)
+    assert_close(g, gstar, tol, gate, "decoded gradient")
     G = hip.ws.slab_grads().cpu().numpy()
-    worst = max(rel_l2(G[q], ref) for q, ref in enumerate(sg))
-    assert worst <= tol, ("slab", worst)
+    for q, ref in enumerate(sg):
+        assert_close(G[q], ref, tol, gate_for(), ("slab", q))
     M = hip.ws.messages().cpu().numpy()
-    worst = max(rel_l2(M[node], ref) for node, ref in enumerate(msgs) if ref is not None)
-    assert worst <= tol, ("message", worst)
+    for node, ref in enumerate(msgs):
+        if ref is not None:
+            assert_close(M[node], ref, tol, gate, ("message", node))
 
 
 def _gd_steps(hip, orc, cfg, data, steps, check_at, tol):
@@ -55,9 +57,9 @@ def _gd_steps(hip, orc, cfg, data, steps, check_at, tol):
         if step in check_at:
             w_host = w_dev.cpu().numpy()
             g = hip.gradient(w_dev, mask)
-            err = rel_l2(g, orc.full_gradient(w_host))
-            print(f"step {step}: rel-L2 {err:.2e}", flush=True)
-            assert err <= tol, (step, err)
+            ref = orc.full_gradient(w_host)
+            print(f"step {step}: rel-L2 {rel_l2(g, ref):.2e}", flush=True)
+            assert_close(g, ref, tol, gate_for(hip.info.gamma, hip.info.L), ("decoded gradient", step))
         else:
             hip.gradient(w_dev, mask)
         cr.cr_gd_update(hip.plan, w_dev, hip.g, lr)
@@ -78,6 +80,40 @@ def test_cfg2_full():
     _, ner = _gd_steps(hip, orc, cfg, data, 50, {0, 1, 2, 10, 25, 49}, 1e-4)
     assert all(b < a for a, b in zip(ner, ner[1:]))      # normalised error rate, eq. (8), falls at every step
     assert ner[-1] < 0.05 * ner[0]
+    hip.close()
+
+
+def test_cfg2_gd_run_full():
+    """The call the benchmark times: cr_gd_run on configuration 2 at full size, the gradient step riding in the decode launch.
+    After every batch of four steps the model equals, bit for bit, the one the step-by-step calls (gradients, encode, decode,
+    update kernel) produce, and follows uncoded fp64 gradient descent from the oracle."""
+    from oracle import native
+
+    torch = _torch()
+    cfg = wl.config("cfg2")
+    data = wl.make_dataset(cfg, threads=16)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    assert (hip.info.split_kind, hip.info.stage1_staged) == (cr.CR_SPLIT_SHARED_CELLS, 1) and hip.info.l2_sharing == 1
+    rng = wl.mask_stream(cfg)
+    lr = float(cfg["lr"])
+    w_run = torch.from_numpy(data["w0"]).cuda()
+    w_steps = torch.from_numpy(data["w0"]).cuda()
+    g_run = torch.empty_like(hip.g)
+    w_ref = data["w0"].astype(np.float64)
+    for batch in range(3):
+        masks = np.stack([wl.draw_mask(rng, cfg["L"], cfg["n"], cfg["s"]) for _ in range(4)])
+        cr.cr_gd_run(hip.plan, hip.X, hip.y, w_run, g_run, masks, lr)
+        for mask in masks:
+            hip.gradient(w_steps, mask)
+            cr.cr_gd_update(hip.plan, w_steps, hip.g, lr)
+        cr.cr_synchronize(hip.plan)
+        assert torch.equal(w_run, w_steps) and torch.equal(g_run, hip.g), batch
+        for _ in masks:                                  # exact gradient descent; the oracle's row loop takes the model in fp32
+            w_ref = w_ref - lr * native.full_gradient(data["X"], data["y"], w_ref.astype(np.float32), cr.CR_LINEAR)
+        err = rel_l2(w_run.cpu().numpy(), w_ref)
+        print(f"after {4 * (batch + 1)} steps: model rel-L2 vs uncoded fp64 GD {err:.2e}", flush=True)
+        assert err <= 1e-5, (batch, err)
+    assert rel_l2(w_run.cpu().numpy(), data["w0"]) > 1e-2
     hip.close()
 
 
@@ -168,7 +204,11 @@ def test_gradient_coding_twenty_workers_full():
 
 
 def test_cfg4_full():
-    """Aggregation only: L=2, n=8, s=2 (72 workers), 248 partition-gradient vectors of length 2^24, 20 random masks."""
+    """Aggregation only: L=2, n=8, s=2 (72 workers), 248 partition-gradient vectors of length 2^24, 20 random masks.  The decoded
+    vector is checked on every column under every mask (it is the sum of all atoms whatever the mask); for the first two masks
+    every message and the decoded vector are compared on every column with the oracle, run in column chunks on the host."""
+    from concurrent.futures import ThreadPoolExecutor
+
     torch = _torch()
     cfg = wl.config("cfg4")
     L, n, s, d = cfg["L"], cfg["n"], cfg["s"], cfg["d"]
@@ -185,30 +225,47 @@ def test_cfg4_full():
     total = atoms_dev.double().sum(dim=0)
     del atoms_dev
     g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
-    cols = np.r_[0:128, (1 << 23) - 64:(1 << 23) + 64, 12_345_678:12_345_678 + 256, d - 128:d]
-    cols_dev = torch.from_numpy(cols).cuda()
-    Gs = G_dev[:, cols_dev].cpu().numpy().astype(np.float64)
-    ng = []
-    for node in range(72):
-        acc = np.zeros(len(cols))
-        for q, (nd, _, _, c) in enumerate(orc.slabs):
-            if nd == node:
-                acc += float(c) * Gs[q]
-        ng.append(acc)
     rng = wl.mask_stream(cfg)
+    gate = gate_for(ws.info.gamma, L)
+    kept = []                                            # (mask, messages, decoded vector) of the first two masks, on the host
     for trial in range(20):
         mask = wl.draw_mask(rng, L, n, s)
         cr.cr_load_partial_grads(plan, G_dev)
         cr.cr_encode_tree(plan, mask)
         cr.cr_decode_root(plan, g_dev)
         cr.cr_synchronize(plan)
-        msgs, g_ref = orc.execute(ng, mask)
-        assert rel_l2(g_dev[cols_dev].cpu().numpy(), g_ref) <= 1e-4
         err = float((g_dev.double() - total).norm() / total.norm())        # all 2^24 columns: the sum of all atoms, whatever the mask
-        assert err <= 1e-4, (trial, err)
-        if trial % 5 == 0:
-            M = ws.messages()[:, cols_dev].cpu().numpy()
+        worst = float((g_dev.double() - total).abs().max() / total.square().mean().sqrt())
+        assert err <= gate and worst <= 10 * gate, (trial, err, worst)
+        if trial < 2:
+            kept.append((mask, ws.messages().cpu().numpy(), g_dev.cpu().numpy()))
+    G = G_dev.cpu().numpy()
+    cr.cr_plan_destroy(plan)
+
+    def check(lo):
+        hi = min(d, lo + (1 << 18))
+        ng = [np.zeros(hi - lo) for _ in range(72)]
+        for q, (nd, _, _, c) in enumerate(orc.slabs):
+            ng[nd] += float(c) * G[q, lo:hi].astype(np.float64)
+        seen = 0.0
+        for mask, M, g in kept:
+            msgs, g_ref = orc.execute(ng, mask)
+            assert rel_l2(g[lo:hi], g_ref) <= gate, (lo, "decoded")
             for node, ref in enumerate(msgs):
                 if ref is not None:
-                    assert rel_l2(M[node], ref) <= 1e-4
-    cr.cr_plan_destroy(plan)
+                    err = rel_l2(M[node, lo:hi], ref)
+                    dev = float(np.max(np.abs(M[node, lo:hi] - ref)) / np.sqrt(np.mean(ref * ref)))
+                    assert err <= gate and dev <= 10 * gate, (lo, node, err, dev)
+                    seen = max(seen, err)
+        return seen
+
+    with ThreadPoolExecutor(max_workers=16) as ex:       # numpy releases the interpreter lock; chunks are independent
+        seen = list(ex.map(check, range(0, d, 1 << 18)))
+    print(f"all {sum(int(m is not None) for m in orc.execute([np.zeros(1)] * 72, kept[0][0])[0])} messages x 2^24 columns x 2 masks: "
+          f"worst chunk rel-L2 {max(seen):.2e}", flush=True)
+
+
+def test_zz_report_what_the_gates_saw():
+    """Not a check: prints the largest relative L2 error and element-wise deviation every kind of row showed in this session."""
+    for kind, (err, worst) in sorted(WORST.items()):
+        print(f"{kind}: worst rel-L2 {err:.2e}, worst max|delta|/rms {worst:.2e}", flush=True)

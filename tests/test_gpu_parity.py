@@ -5,7 +5,7 @@ import pytest
 
 import paper_1902_01981_amd as cr
 from cr_inputs import workloads as wl
-from _harness import TOL, HipPath, OraclePath, rel_l2
+from _harness import TOL, WORST, HipPath, OraclePath, assert_close, gate_for, rel_l2
 
 pytestmark = pytest.mark.gpu
 B_PRINTED = np.array([[0.5, 1, 0], [0, 1, -1], [0.5, 0, 1]])
@@ -27,15 +27,16 @@ def _check_iteration(hip, orc, w, mask, tol, check_rows=True):
     msgs, g_cr = orc.execute(ng, mask)
     gstar = orc.full_gradient(w)
     assert rel_l2(g_cr, gstar) < 1e-9                    # the oracle's tree result is the plain definition
-    assert rel_l2(g, gstar) <= tol, ("decoded gradient", rel_l2(g, gstar))
+    gate = gate_for(hip.info.gamma, hip.info.L)
+    assert_close(g, gstar, tol, gate, "decoded gradient")
     if check_rows:
         G = hip.ws.slab_grads().cpu().numpy()
         for q, ref in enumerate(sg):
-            assert rel_l2(G[q], ref) <= tol, ("slab", q, rel_l2(G[q], ref))
+            assert_close(G[q], ref, tol, gate_for(), ("slab", q))
         M = hip.ws.messages().cpu().numpy()
         for node, ref in enumerate(msgs):
             if ref is not None:
-                assert rel_l2(M[node], ref) <= tol, ("message", node, rel_l2(M[node], ref))
+                assert_close(M[node], ref, tol, gate, ("message", node))
     return g
 
 
@@ -55,18 +56,18 @@ def test_cfg1_every_mask():
     count = 0
     for mask in wl.enumerate_masks(cfg["L"], cfg["n"], cfg["s"]):
         g = hip.gradient(w_dev, mask)
-        assert rel_l2(g, gstar) <= 1e-4, (mask, rel_l2(g, gstar))
+        assert_close(g, gstar, 1e-4, gate_for(hip.info.gamma, 2), "decoded gradient")
         if count % 16 == 0:
             msgs, _ = orc.execute(ng, mask)
             M = hip.ws.messages().cpu().numpy()
             for node, ref in enumerate(msgs):
                 if ref is not None:
-                    assert rel_l2(M[node], ref) <= 1e-4
+                    assert_close(M[node], ref, 1e-4, gate_for(hip.info.gamma, 2), ("message", node))
         count += 1
     assert count == 256
     G = hip.ws.slab_grads().cpu().numpy()
     for q, ref in enumerate(sg):
-        assert rel_l2(G[q], ref) <= 1e-4
+        assert_close(G[q], ref, 1e-4, gate_for(), ("slab", q))
     hip.close()
 
 
@@ -114,6 +115,8 @@ CASES = [
     ("wide-rows-bf16", 2, 4, 1, 500, 50_008, cr.CR_LOGISTIC, cr.CR_BF16, None),
     ("wide-rows-odd", 1, 3, 1, 200, 25_001, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_EQUAL_RANGES, 40)),
     ("cr-12x2-s3", 2, 12, 3, 31_200, 320, cr.CR_LOGISTIC, cr.CR_F32, None),       # the paper's (12,2) tree, 156 workers, 3 stragglers per group
+    ("cr-12x2-s2", 2, 12, 2, 15_611, 1_000, cr.CR_LINEAR, cr.CR_F32, None),       # ... 2 per group
+    ("cr-12x2-s5", 2, 12, 5, 49_920, 432, cr.CR_LOGISTIC, cr.CR_F32, None),       # ... 5 per group (resiliency 5/12, 49 920 points as in the network experiment): 36 holders per row
     # rows staged through LDS and shared by the holders in one workgroup
     ("staged-2-holders", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # 10 chunks per thread, odd and even step counts
     ("staged-2-holders-odd-d", 2, 4, 1, 2_003, 9_999, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 64)),
@@ -217,6 +220,40 @@ def test_device_resident_gd_loop_and_run_time_model_masks():
     hip.close()
 
 
+@pytest.mark.parametrize("d,m,model", [(5, 900, cr.CR_LINEAR), (1_003, 2_400, cr.CR_LOGISTIC), (9_999, 2_003, cr.CR_LINEAR), (10, 480, cr.CR_LINEAR)])
+def test_gd_run_fused_step_with_ragged_widths(d, m, model):
+    """cr_gd_run without the convergence measures lets the gradient step ride in the decode launch.  With d not a multiple of 4 the
+    row's last chunk overlaps its neighbour and only the owner of a column may step it: compared bit for bit with separate decode
+    and update calls, and with uncoded fp64 gradient descent from the oracle."""
+    torch = _torch()
+    L, n, s = 2, 3, 1
+    cfg = wl.config("cfg3" if model == cr.CR_LOGISTIC else "cfg2", L=L, n=n, s=s, m=m, d=d, model=model,
+                    w0_std=None if model == cr.CR_LOGISTIC else 1.0, seed=31_000 + d)
+    data = wl.make_dataset(cfg)
+    hip = HipPath(L, n, s, data["X"], data["y"], model, cr.CR_F32)
+    orc = OraclePath(L, n, s, data["X"], data["y"], model)
+    steps = 9
+    lr = 0.5 / (m * (1 + np.sqrt(d / m)) ** 2) * (4.0 if model == cr.CR_LOGISTIC else 1.0)      # inside 2 / lambda_max(X^T X)
+    rng = wl.mask_stream(cfg)
+    masks = np.stack([wl.draw_mask(rng, L, n, s) for _ in range(steps)])
+    w_a = torch.from_numpy(data["w0"]).cuda()
+    for t in range(steps):                               # separate calls: decode, then the update kernel
+        hip.gradient(w_a, masks[t])
+        cr.cr_gd_update(hip.plan, w_a, hip.g, lr)
+    g_a = hip.g.clone()
+    w_b = torch.from_numpy(data["w0"]).cuda()
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_b, hip.g, masks[:4], lr)       # two calls: the loop can be resumed
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_b, hip.g, masks[4:], lr)
+    cr.cr_synchronize(hip.plan)
+    assert torch.equal(w_a, w_b) and torch.equal(g_a, hip.g)
+    w = data["w0"].astype(np.float64)
+    for t in range(steps):
+        w = w - lr * orc.full_gradient(w)
+    assert rel_l2(w_b.cpu().numpy(), w) <= 1e-5, rel_l2(w_b.cpu().numpy(), w)
+    assert rel_l2(w_b.cpu().numpy(), data["w0"]) > 1e-3                   # and the model did move
+    hip.close()
+
+
 def test_aggregation_only():
     """Partition gradients supplied as vectors (L=2, n=8, s=2): encode + decode alone, 20 masks."""
     torch = _torch()
@@ -261,9 +298,10 @@ def test_aggregation_only():
     cr.cr_plan_destroy(plan)
 
 
-@pytest.mark.parametrize("s", [1, 3])
+@pytest.mark.parametrize("s", [1, 2, 3, 5])
 def test_aggregation_only_network_sized(s):
-    """(12,2) tree, 156 workers, vectors of the size of the paper's CNN (117 706 parameters, not a multiple of 4)."""
+    """(12,2) tree, 156 workers, 1 to 5 stragglers per group (5 = the resiliency 5/12 of the network experiment), vectors of the
+    size of the paper's CNN (117 706 parameters, not a multiple of 4)."""
     torch = _torch()
     L, n, d = 2, 12, 117_706
     m = 156 * 40
@@ -288,10 +326,63 @@ def test_aggregation_only_network_sized(s):
         cr.cr_decode_root(plan, g_dev)
         cr.cr_synchronize(plan)
         msgs, g_ref = orc.execute(ng, mask)
-        assert rel_l2(g_dev.cpu().numpy(), g_ref) <= 1e-4
+        gate = gate_for(info.gamma, L)
+        assert_close(g_dev.cpu().numpy(), g_ref, 1e-4, gate, "decoded gradient")
         M = ws.messages().cpu().numpy()
-        assert max(rel_l2(M[node], ref) for node, ref in enumerate(msgs) if ref is not None) <= 1e-4
+        for node, ref in enumerate(msgs):
+            if ref is not None:
+                assert_close(M[node], ref, 1e-4, gate, ("message", node))
     cr.cr_plan_destroy(plan)
+
+
+LAYERS = [("conv1.weight", 3 * 16 * 3 * 3), ("conv1.bias", 16), ("conv2.weight", 16 * 64 * 4 * 4), ("conv2.bias", 64),
+          ("fc1.weight", 64 * 384), ("fc1.bias", 384), ("fc2.weight", 384 * 192), ("fc2.bias", 192), ("fc3.weight", 192 * 10),
+          ("fc3.bias", 10)]
+
+
+@pytest.mark.parametrize("s", [2, 5])
+def test_aggregation_per_layer_of_the_simulated_network(s):
+    """The network of the paper's simulation (two convolutions, three dense layers: 117 706 parameters) aggregated layer by layer,
+    as a training framework hands gradients over: ten vectors of 10 to 73 728 entries, several shorter than one workgroup's
+    columns, some not multiples of 4, each through its own plan on the (12,2) tree over 49 920 data points."""
+    torch = _torch()
+    L, n, m = 2, 12, 49_920
+    assert sum(size for _, size in LAYERS) == 117_706
+    orc = OraclePath(L, n, s, np.zeros((m, 1), dtype=np.float32), np.zeros(m, dtype=np.float32), cr.CR_LINEAR)
+    cuts, member = wl.atoms_of([b for (_, b, _, _) in orc.slabs], [e for (_, _, e, _) in orc.slabs])
+    rng = np.random.default_rng(50 + s)
+    masks = [wl.draw_mask(rng, L, n, s) for _ in range(3)]
+    masks[2][::n] = 0                                    # fewer than s stragglers in every group: the padded decode rows
+    B_plan = None
+    for k, (name, d) in enumerate(LAYERS):
+        # the first plan searches the code; the others are handed its B (the search does not depend on d)
+        plan = cr.cr_plan_ex(L, n, s, m, d, model=cr.CR_AGGREGATE_ONLY, B=B_plan)
+        if B_plan is None:
+            B_plan = cr.cr_plan_get_B(plan)
+            np.testing.assert_allclose(B_plan, orc.B, atol=1e-12)
+        ws = cr.Workspace(plan)
+        assert ws.info.num_slabs == len(orc.slabs)
+        atoms = wl.atom_vectors(7_000 + 10 * s + k, len(cuts) - 1, 0, d)
+        G = np.stack([atoms[idx].sum(axis=0, dtype=np.float32) for idx in member])
+        G_dev = torch.from_numpy(G).cuda()
+        g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
+        ng = [np.zeros(d) for _ in range(156)]
+        for q, (nd, _, _, c) in enumerate(orc.slabs):
+            ng[nd] += float(c) * G[q].astype(np.float64)
+        gate = gate_for(ws.info.gamma, L)
+        for mask in masks:
+            cr.cr_load_partial_grads(plan, G_dev)
+            cr.cr_encode_tree(plan, mask)
+            cr.cr_decode_root(plan, g_dev)
+            cr.cr_synchronize(plan)
+            msgs, g_ref = orc.execute(ng, mask)
+            assert_close(g_dev.cpu().numpy(), g_ref, 1e-4, gate, ("decoded gradient", name))
+            assert_close(g_dev.cpu().numpy(), atoms.astype(np.float64).sum(0), 1e-4, gate, ("sum of all atoms", name))
+            M = ws.messages().cpu().numpy()
+            for node, ref in enumerate(msgs):
+                if ref is not None:
+                    assert_close(M[node], ref, 1e-4, gate, ("message", name, node))
+        cr.cr_plan_destroy(plan)
 
 
 def test_aggregation_only_long_vectors():
@@ -449,3 +540,9 @@ def test_read_bandwidth_probe_reads_every_word():
     with pytest.raises(cr.CodedReduceError):
         cr.cr_probe_read_bandwidth(src, 1024, sink)
 
+
+
+def test_zz_report_what_the_gates_saw():
+    """Not a check: prints the largest relative L2 error and element-wise deviation every kind of row showed in this session."""
+    for kind, (err, worst) in sorted(WORST.items()):
+        print(f"{kind}: worst rel-L2 {err:.2e}, worst max|delta|/rms {worst:.2e}", flush=True)
