@@ -189,6 +189,26 @@ int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
 int cr_gd_run(cr_plan_t *plan, const void *X_dev, const float *y_dev, float *w_dev, float *g_dev, const uint8_t *masks_host,
               int steps, float lr, const float *w_star_or_null, float *metrics_or_null);
 
+/* ---- aggregation without any allocation ----------------------------------------------------------------------------------------
+ * For callers that cannot allocate or bind device memory: code under HIP stream capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  cr_aggregate_static is cr_load_partial_grads + cr_encode_tree + cr_decode_root in one call, with everything those
+ * keep in a workspace -- the per-call encode program and the messages M[N][d] -- held in a device array that is part of the library
+ * itself (CR_STATIC_SCRATCH_BYTES; each GPU the library runs on holds one until the process ends).  The plan needs no workspace.
+ * The call allocates and frees nothing on the device or in pinned memory and records no copy: the program reaches the device as
+ * kernel arguments, so all it enqueues on hip_stream is kernel launches (a handful of small ones, encode, decode).
+ *   plan        any plan; its model is not consulted (no stage 1 runs)
+ *   G_dev       device, S x d floats, 16-byte aligned: the slab gradients, read in place
+ *   mask_host   host, N bytes, non-zero = straggler; read before the call returns
+ *   g_dev       device, d floats: receives the decoded gradient (the same bits cr_decode_root gives for the same G and mask)
+ *   hip_stream  a hipStream_t (NULL = the default stream)
+ * Limits: the messages must fit, N * d * 4 <= CR_STATIC_SCRATCH_BYTES - 64 KiB (the paper's network, 156 workers x 117 706
+ * parameters, does), and the encode program (28 bytes per slab and per worker) must fit 64 KiB: CR_E_INVAL otherwise, before
+ * anything is enqueued.  CR_E_UNDECODABLE as for cr_encode_tree.  All calls on one GPU share that GPU's array, whatever the plan:
+ * calls that overlap in time on one GPU (two streams, two threads) race.  The array keeps the previous call's contents; nothing
+ * in it needs clearing, since every message row that is read was written earlier in the same call. */
+#define CR_STATIC_SCRATCH_BYTES ((size_t)96 << 20)
+int cr_aggregate_static(cr_plan_t *plan, const float *G_dev, const uint8_t *mask_host, float *g_dev, void *hip_stream);
+
 /* ---- results kept in the workspace (device pointers, valid while the workspace is) --------------------------- */
 int cr_get_slab_grads(const cr_plan_t *plan, const float **G_dev); /* S x d */
 int cr_get_messages(const cr_plan_t *plan, const float **M_dev);   /* N x d, row = worker id */

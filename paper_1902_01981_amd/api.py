@@ -28,7 +28,7 @@ EXPORTS = [
     "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
-    "cr_probe_read_bandwidth",
+    "cr_probe_read_bandwidth", "cr_aggregate_static",
 ]
 
 
@@ -80,6 +80,7 @@ def load_library():
         lib.cr_decode_root.argtypes = [vp, vp]
         lib.cr_gd_update.argtypes = [vp, vp, vp, ctypes.c_float]
         lib.cr_gd_run.argtypes = [vp, vp, vp, vp, vp, vp, c_int, ctypes.c_float, vp, vp]
+        lib.cr_aggregate_static.argtypes = [vp, vp, vp, vp, vp]
         lib.cr_get_slab_grads.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_get_messages.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_profile_enable.argtypes = [vp, c_int]
@@ -273,6 +274,18 @@ def cr_gd_run(plan: int, X, y, w, g, masks, lr: float, w_star=None, metrics=None
                                     _dev(w, "w", "f32", info.d), _dev(g, "g", "f32", info.d), m.ctypes.data, m.shape[0], lr,
                                     _dev(w_star, "w_star", "f32", info.d, optional=True),
                                     _dev(metrics, "metrics", "f32", 2 * m.shape[0], optional=True)))
+
+
+CR_STATIC_SCRATCH_BYTES = 96 << 20
+
+
+def cr_aggregate_static(plan: int, G, straggler_mask, g, stream: int = 0) -> None:
+    info = cr_plan_info(plan)
+    mask = np.ascontiguousarray(straggler_mask, dtype=np.uint8)
+    if mask.shape != (info.num_workers,):
+        raise ValueError("mask must have one byte per worker")
+    _check(load_library().cr_aggregate_static(plan, _dev(G, "G", "f32", info.num_slabs * info.d), mask.ctypes.data,
+                                              _dev(g, "g", "f32", info.d), stream))
 
 
 def cr_get_slab_grads(plan: int) -> int:

@@ -97,6 +97,7 @@ struct cr_plan_s {
     int num_dec_terms = 0;
 
     bool have_grads = false, have_messages = false;
+    std::vector<char> static_program;              // host copy of the encode program of cr_aggregate_static (ordinary memory)
 
     // timing
     unsigned profiling = 0;                         // bit k: launches of kernel id k are bracketed by events
@@ -672,27 +673,24 @@ int cr_load_partial_grads(cr_plan_t *p, const float *G)
     return CR_OK;
 }
 
-int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
+namespace {
+
+struct ProgramCounts { int64_t active_slabs = 0, active_msgs = 0; int dec_terms = 0; };
+
+// Turns a straggler mask into the encode program of one iteration, written into the host block h (program_bytes long, laid out
+// by compute_layout): the post-order term list of every level-1 sub-tree and the master's decode terms.  Any group beyond
+// tolerance fails the call before anything is written (CR_E_UNDECODABLE).
+int build_program(cr_plan_t *p, const uint8_t *mask, char *h, ProgramCounts *counts)
 {
-    if (!p || !mask) return fail(CR_E_INVAL, "NULL argument");
-    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
-    if (!p->have_grads) return fail(CR_E_STATE, "no partial gradients yet");
     const int n = p->n, L = p->L;
     const int32_t N = p->tree.N, groups = N / n;
-
-    // decode row of every sibling group; any group beyond tolerance fails the call before anything is enqueued
+    // decode row of every sibling group
     std::vector<const double *> rows(groups);
     for (int32_t g = 0; g < groups; ++g) {
         int rc = group_decode_row(p, mask + static_cast<size_t>(g) * n, &rows[g]);
         if (rc == CR_E_UNDECODABLE) return fail(rc, "sibling group " + std::to_string(g) + " has more than s stragglers");
         if (rc != CR_OK) return rc;
     }
-
-    // host staging slot (pinned); wait until the copy that last used it has finished
-    const int slot = p->staging_next;
-    p->staging_next = (slot + 1) % kStagingSlots;
-    if (p->staging_used[slot]) CR_HIP(hipEventSynchronize(p->staging_done[slot]));
-    char *h = p->h_staging + static_cast<size_t>(slot) * p->program_bytes;
     int32_t *t_slab = reinterpret_cast<int32_t *>(h + p->off_slab);
     int32_t *t_level = reinterpret_cast<int32_t *>(h + p->off_level);
     int32_t *t_row = reinterpret_cast<int32_t *>(h + p->off_row);
@@ -704,7 +702,6 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
 
     // post-order program of every level-1 sub-tree
     size_t nt = 0;
-    int64_t active_slabs = 0, active_msgs = 0;
     struct Frame { int32_t node; int level; int next_child; };
     std::vector<Frame> stack;
     for (int i = 0; i < n; ++i) {
@@ -734,8 +731,8 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
             t_level[nt - 1] = level;                      // the node's last term finishes it
             t_row[nt - 1] = node;
             t_acoef[nt - 1] = acoef;
-            active_slabs += se - sb;
-            active_msgs += 1;
+            counts->active_slabs += se - sb;
+            counts->active_msgs += 1;
         }
         real_terms = nt - static_cast<size_t>(sub[i]);
         while (nt % cr::kEncodeUnroll != 0) {             // pad with no-op terms on an already fetched slab
@@ -747,22 +744,53 @@ int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
     int ndec = 0;
     for (int j = 0; j < n; ++j)
         if (!mask[j] && rows[0][j] != 0.0) dec[ndec++] = {j, 0, rows[0][j]};
-    p->num_dec_terms = ndec;
+    counts->dec_terms = ndec;
+    return CR_OK;
+}
+
+// the program's arrays as the encode kernel takes them, for a program block at device address d_program
+cr::EncProgram program_view(const cr_plan_t *p, const char *d_program)
+{
+    cr::EncProgram prog;
+    prog.slab = reinterpret_cast<const int32_t *>(d_program + p->off_slab);
+    prog.level = reinterpret_cast<const int32_t *>(d_program + p->off_level);
+    prog.row = reinterpret_cast<const int32_t *>(d_program + p->off_row);
+    prog.coef = reinterpret_cast<const double *>(d_program + p->off_coef);
+    prog.acoef = reinterpret_cast<const double *>(d_program + p->off_acoef);
+    prog.sub_begin = reinterpret_cast<const int32_t *>(d_program + p->off_sub);
+    prog.sub_end = prog.sub_begin + p->n;
+    return prog;
+}
+
+}  // namespace
+
+int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
+{
+    if (!p || !mask) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (!p->have_grads) return fail(CR_E_STATE, "no partial gradients yet");
+    // any group beyond tolerance fails the call before anything is enqueued; checked before a staging slot is taken
+    for (int32_t g = 0; g < p->tree.N / p->n; ++g) {
+        int cnt = 0;
+        for (int j = 0; j < p->n; ++j) cnt += mask[static_cast<size_t>(g) * p->n + j] ? 1 : 0;
+        if (cnt > p->s) return fail(CR_E_UNDECODABLE, "sibling group " + std::to_string(g) + " has more than s stragglers");
+    }
+    // host staging slot (pinned); wait until the copy that last used it has finished
+    const int slot = p->staging_next;
+    if (p->staging_used[slot]) CR_HIP(hipEventSynchronize(p->staging_done[slot]));
+    char *h = p->h_staging + static_cast<size_t>(slot) * p->program_bytes;
+    ProgramCounts counts;
+    int rc = build_program(p, mask, h, &counts);
+    if (rc != CR_OK) return rc;
+    p->staging_next = (slot + 1) % kStagingSlots;
+    p->num_dec_terms = counts.dec_terms;
 
     CR_HIP(hipMemcpyAsync(p->d_program, h, p->program_bytes, hipMemcpyHostToDevice, p->stream));
     CR_HIP(hipEventRecord(p->staging_done[slot], p->stream));
     p->staging_used[slot] = true;
 
-    LaunchTimer t(p, CR_K_ENCODE, (active_slabs + active_msgs) * p->d * 4);
-    cr::EncProgram prog;
-    prog.slab = reinterpret_cast<const int32_t *>(p->d_program + p->off_slab);
-    prog.level = reinterpret_cast<const int32_t *>(p->d_program + p->off_level);
-    prog.row = reinterpret_cast<const int32_t *>(p->d_program + p->off_row);
-    prog.coef = reinterpret_cast<const double *>(p->d_program + p->off_coef);
-    prog.acoef = reinterpret_cast<const double *>(p->d_program + p->off_acoef);
-    prog.sub_begin = reinterpret_cast<const int32_t *>(p->d_program + p->off_sub);
-    prog.sub_end = prog.sub_begin + n;
-    CR_HIP(cr::launch_encode(p->G_src, p->d_M, prog, n, L, p->d, p->stream));
+    LaunchTimer t(p, CR_K_ENCODE, (counts.active_slabs + counts.active_msgs) * p->d * 4);
+    CR_HIP(cr::launch_encode(p->G_src, p->d_M, program_view(p, p->d_program), p->n, p->L, p->d, p->stream));
     t.done();
     p->have_messages = true;
     return CR_OK;
@@ -823,6 +851,35 @@ int cr_gd_run(cr_plan_t *p, const void *X, const float *y, float *w, float *g, c
             tm.done();
         }
     }
+    return CR_OK;
+}
+
+int cr_aggregate_static(cr_plan_t *p, const float *G, const uint8_t *mask, float *g, void *hip_stream)
+{
+    static_assert(CR_STATIC_SCRATCH_BYTES == cr::kStaticScratchBytes, "the header states the size of the library's device array");
+    if (!p || !G || !mask || !g) return fail(CR_E_INVAL, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(G) % 16 != 0) return fail(CR_E_INVAL, "G must be 16-byte aligned");
+    if (p->program_bytes == 0) {                        // offsets of the program's arrays: host arithmetic only
+        size_t unused = 0;
+        compute_layout(p, &unused);
+    }
+    const size_t msg_bytes = static_cast<size_t>(p->tree.N) * static_cast<size_t>(p->d) * sizeof(float);
+    if (p->program_bytes > cr::kStaticProgramBytes)
+        return fail(CR_E_INVAL, "cr_aggregate_static: the encode program of this tree (" + std::to_string(p->program_bytes) + " bytes) exceeds 64 KiB");
+    if (msg_bytes > cr::kStaticScratchBytes - cr::kStaticProgramBytes)
+        return fail(CR_E_INVAL, "cr_aggregate_static: N * d * 4 = " + std::to_string(msg_bytes) + " bytes of messages exceed the library's device array (" +
+                                    std::to_string(cr::kStaticScratchBytes - cr::kStaticProgramBytes) + " bytes)");
+    if (p->static_program.size() != p->program_bytes) p->static_program.assign(p->program_bytes, 0);
+    ProgramCounts counts;
+    int rc = build_program(p, mask, p->static_program.data(), &counts);
+    if (rc != CR_OK) return rc;
+    char *base = nullptr;
+    CR_HIP(cr::static_scratch(&base));                  // this device's copy of the array; never the array's name
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float *M = reinterpret_cast<float *>(base + cr::kStaticProgramBytes);
+    CR_HIP(cr::launch_upload(base, p->static_program.data(), p->program_bytes, stream));
+    CR_HIP(cr::launch_encode(G, M, program_view(p, base), p->n, p->L, p->d, stream));
+    CR_HIP(cr::launch_decode(M, g, reinterpret_cast<const cr::DecTerm *>(base + p->off_dec), counts.dec_terms, p->d, nullptr, 0.f, stream));
     return CR_OK;
 }
 

@@ -77,6 +77,16 @@ hipError_t launch_update(float *w, const float *g, float lr, int64_t d, hipStrea
 // plain streaming read of n16 16-byte words; every workgroup writes its sum to sink[workgroup] (kStreamGroups workgroups)
 constexpr int kStreamGroups = 256 * 8;
 hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStream_t stream);
+// ---- the library's own device memory, for callers that cannot allocate -------------------------------------------------------
+// A file-scope device array of kStaticScratchBytes (every GPU the library runs on holds its own copy until the process ends).
+// static_scratch returns its address on the CURRENT device (looked up once per device, no allocation) in *ptr.
+constexpr size_t kStaticProgramBytes = size_t(64) << 10;                 // head of the array: one encode program
+constexpr size_t kStaticScratchBytes = size_t(96) << 20;                 // the whole array; messages follow the program
+hipError_t static_scratch(char **ptr);
+// copies `bytes` (a multiple of 4) from host memory to the device address dst through kernel arguments: launches only, no
+// staging buffer, no memcpy node; the host bytes are consumed before the call returns
+hipError_t launch_upload(char *dst, const char *src_host, size_t bytes, hipStream_t stream);
+
 // one wavefront per workgroup; out[workgroup id] = (die the workgroup ran on) << 16 | (shader engine and compute unit inside the die)
 hipError_t launch_placement_probe(uint32_t *out, int groups, hipStream_t stream);
 hipError_t launch_update_metrics(float *w, const float *g, float lr, const float *w_star, float *metrics, int64_t d, hipStream_t stream);

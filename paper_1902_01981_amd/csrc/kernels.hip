@@ -18,6 +18,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <cstring>
+
 namespace cr {
 
 namespace {
@@ -952,6 +955,57 @@ hipError_t launch_stream_read(const void *src, size_t n16, float *sink, hipStrea
 {
     stream_read_kernel<<<kStreamGroups, 256, 0, stream>>>(static_cast<const f4a *>(src), n16, sink);
     return hipGetLastError();
+}
+
+// ---- device memory owned by the library --------------------------------------------------------------------------------
+// For callers that cannot allocate (under stream capture, in serving loops): the scratch the aggregation needs beyond its inputs
+// and outputs -- one encode program and the message rows M[N][d] -- lives in this array.  In host code the array's name is only a
+// stand-in; its device address is asked for once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<char *> g_scratch_ptr[kMaxDevices];           // per device: where that device's copy of `scratch` lives
+}  // namespace
+
+hipError_t static_scratch(char **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!sym) return hipErrorInvalidSymbol;
+        p = static_cast<char *>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);    // two threads racing here store the same address
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
+// A block of host bytes travels as a kernel argument (kernel arguments are copied when the launch is enqueued) and one
+// workgroup writes it out with vector stores.
+struct UploadBlock { uint32_t word[960]; };
+__global__ void __launch_bounds__(256) upload_kernel(uint32_t *__restrict__ dst, UploadBlock block, int nwords)
+{
+    for (int i = threadIdx.x; i < nwords; i += 256) dst[i] = block.word[i];
+}
+
+hipError_t launch_upload(char *dst, const char *src_host, size_t bytes, hipStream_t stream)
+{
+    for (size_t off = 0; off < bytes; off += sizeof(UploadBlock)) {
+        UploadBlock block;
+        const size_t len = bytes - off < sizeof(UploadBlock) ? bytes - off : sizeof(UploadBlock);
+        std::memcpy(block.word, src_host + off, len);
+        upload_kernel<<<1, 256, 0, stream>>>(reinterpret_cast<uint32_t *>(dst + off), block, static_cast<int>(len / 4));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // ---- where do workgroups run? -----------------------------------------------------------------------------------------

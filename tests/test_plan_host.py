@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "codedreduce.h")) as f:
         header = f.read()
     declared = set(re.findall(r"^(?:int|void|const char \*)\s*\**(cr_\w+)\(", header, flags=re.M))
-    assert declared == set(cr.EXPORTS) and len(declared) == 27
+    assert declared == set(cr.EXPORTS) and len(declared) == 28
     lib = ctypes.CDLL(cr.LIB_PATH)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -398,3 +398,23 @@ def test_binding_rejects_wrong_device_buffers(plans):
         cr.cr_gd_run(p, FakeDeviceTensor(torch.bfloat16, 120_000), ok(1200), ok(100), ok(100), masks, 0.1)
     with pytest.raises(TypeError):
         cr.cr_bind_workspace(p, np.zeros(16), 16)
+
+
+def test_static_aggregation_rejects_what_does_not_fit(plans):
+    """cr_aggregate_static works out of a device array of fixed size inside the library: sizes beyond it are refused on the host,
+    before any device call (so this runs without a GPU), and so are undecodable masks."""
+    lib = cr.load_library()
+    fits = 96 * 2 ** 20 - 64 * 2 ** 10
+    big = plans(2, 12, 3, 156 * 40, fits // (156 * 4) + 1, model=cr.CR_AGGREGATE_ONLY)      # messages one column too wide
+    mask = np.zeros(156, dtype=np.uint8)
+    assert lib.cr_aggregate_static(big, 256, mask.ctypes.data, 256, None) == cr.CR_E_INVAL and "exceed" in cr.cr_last_error()
+    many = plans(3, 12, 1, 40_000, 4, model=cr.CR_AGGREGATE_ONLY)                           # 1884 workers: the program exceeds 64 KiB
+    mask = np.zeros(1884, dtype=np.uint8)
+    assert lib.cr_aggregate_static(many, 256, mask.ctypes.data, 256, None) == cr.CR_E_INVAL and "64 KiB" in cr.cr_last_error()
+    ok = plans(2, 3, 1, 1200, 100, model=cr.CR_AGGREGATE_ONLY)
+    mask = np.zeros(12, dtype=np.uint8)
+    mask[[3, 4]] = 1
+    assert lib.cr_aggregate_static(ok, 256, mask.ctypes.data, 256, None) == cr.CR_E_UNDECODABLE
+    assert lib.cr_aggregate_static(ok, 250, mask.ctypes.data, 256, None) == cr.CR_E_INVAL     # misaligned G
+    assert lib.cr_aggregate_static(ok, 0, mask.ctypes.data, 256, None) == cr.CR_E_INVAL
+    assert cr.CR_STATIC_SCRATCH_BYTES == 96 << 20
