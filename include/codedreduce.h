@@ -123,10 +123,12 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *   CR_SPLIT_ROW_CELLS     value = rows per cell: every slab is cut on one global grid of that many rows, one piece per team, teams
  *                          ordered by cell so that the holders of the same rows run at the same time.
  *   CR_SPLIT_SHARED_CELLS  value = most rows per cell: the grid is laid between slab boundaries, so every holder of a cell holds
- *                          all of it; 2, 4 or 8 holders (by row width and by (s+1)^L, the most holders a row can have) share a
+ *                          all of it; 2, 3, 4 or 8 holders (by row width and by (s+1)^L, the most holders a row can have) share a
  *                          workgroup, which fetches each row once into LDS for all of them; each still does all of its own
  *                          arithmetic.  One workgroup per compute unit works through a queue of cells (a team then runs
- *                          several pieces).  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.
+ *                          several pieces).  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.  Rows of
+ *                          1537 to 2560 whole chunks (d a multiple of 4) held by 3 or more workers go straight from HBM into LDS
+ *                          (no registers on the way in), 3 holders per workgroup.
  * Default (when this is never called): with s = 0 (no row is held twice) equal ranges, one per resident workgroup; else shared
  * cells where that kernel exists and the problem has at least 128 rows per compute unit and workgroup, with the cell height
  * (64 to 1024 rows) that gives the shortest longest queue; else row cells of about 2 MB of X (96 to 512 rows, fewer for

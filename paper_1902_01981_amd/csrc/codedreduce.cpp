@@ -150,13 +150,13 @@ int query_l2_domains()
 // without a device).  Rows of at most 8 KB get two per unit where registers and LDS let two workgroups stay resident: their steps
 // are short, and the second workgroup fills the gaps around the first one's barriers (measured +10 to +16 % at 2048 columns;
 // longer rows gain nothing).
-int unit_slots(const cr::Stage1Variant *v, int64_t row_bytes, int domains)
+int unit_slots(const cr::Stage1Variant *v, int64_t row_bytes, int64_t d, int domains)
 {
     int dev = 0, cus = 0, resident = 0;
     if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= domains) {
         int slots = cus / domains * domains;
-        if (v && row_bytes <= 8192 && cr::prepare_stage1(*v) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, v->fn[0], v->block(), v->lds_bytes()) == hipSuccess && resident >= 2)
+        if (v && row_bytes <= 8192 && cr::prepare_stage1(*v, d) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, v->fn[0], v->block(), v->lds_bytes(d)) == hipSuccess && resident >= 2)
             slots *= 2;
         (void)hipGetLastError();
         return slots;
@@ -194,7 +194,7 @@ int ensure_split(cr_plan_t *p)
         // shortest; ties go to the taller cell (fewer partial rows).
         kind = CR_SPLIT_SHARED_CELLS;
         const int tpb = p->variant_staged->teams_per_block();
-        const int slots = unit_slots(p->variant_staged, p->d * elem_size(p), domains);
+        const int slots = unit_slots(p->variant_staged, p->d * elem_size(p), p->d, domains);
         value = 512;
         if (p->row_visits / tpb / 64 <= (int64_t(1) << 16)) {       // with longer queues than that the last round no longer matters
             int64_t best = -1;
@@ -224,7 +224,7 @@ int ensure_split(cr_plan_t *p)
     p->split_value_used = value;
     if (kind == CR_SPLIT_SHARED_CELLS) {
         if (p->row_visits / value + 2 * static_cast<int64_t>(p->slabs.size()) > (int64_t(1) << 26)) return fail(CR_E_INVAL, "too many row cells");
-        p->unit_slots = unit_slots(p->variant, p->d * elem_size(p), domains);
+        p->unit_slots = unit_slots(p->variant, p->d * elem_size(p), p->d, domains);
         cr::split_shared_queues(p->slabs, value, domains, teams_per_block, p->unit_slots / domains, p->split);
         // what the staged kernel relies on: every piece of an item covers the same rows
         const cr::Split &sp = p->split;
@@ -567,8 +567,8 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
         int dev = 0, lds = 0;
         CR_HIP(hipGetDevice(&dev));
         CR_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-        if (p->variant->lds_bytes() > static_cast<size_t>(lds)) return fail(CR_E_INVAL, "the stage-1 kernel needs more LDS per workgroup than this device has");
-        CR_HIP(cr::prepare_stage1(*p->variant));
+        if (p->variant->lds_bytes(p->d) > static_cast<size_t>(lds)) return fail(CR_E_INVAL, "the stage-1 kernel needs more LDS per workgroup than this device has");
+        CR_HIP(cr::prepare_stage1(*p->variant, p->d));
     }
     p->stream = static_cast<hipStream_t>(hip_stream);
     p->ws = static_cast<char *>(dev_ptr);

@@ -20,6 +20,7 @@
 
 #include <atomic>
 #include <cstring>
+#include <type_traits>
 
 namespace cr {
 
@@ -425,6 +426,183 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
     }
 }
 
+// ---- stage 1 with rows loaded straight into LDS ------------------------------------------------------------------------
+// The same sharing for rows that start on 16-byte boundaries (fp32, d a multiple of 4), with the fetch done by the load-to-LDS form
+// of the global load (global_load_lds_dwordx4: lane l of a wavefront writes 16 bytes at LDS offset M0 + 16 l).  Nothing passes
+// through registers on its way in, which leaves room for a third holder per workgroup at 10 chunks per thread (168 registers at
+// 768 threads), and the depth of the prefetch is set by LDS alone: a ring of NB rows, one being computed, the others landed or in
+// flight.  One barrier per row:
+//     read row b from its ring slot into registers, dot products, park the partial dots in LDS
+//     wait until this wavefront's loads of row b+1 have landed (rows b+2 .. b+NB-1 stay in flight), barrier
+//     aim the loads of row b+NB at the slot of row b            (every team holds row b in registers)
+//     residuals and rank-1 updates of row b
+// The loads are written as inline assembly so that the compiler neither knows nor guesses which LDS bytes they touch: every wait is
+// written out with the number of loads that may stay in flight.  That count must be exact, so every wavefront issues the same
+// number of loads for every row, also past the end of its queue (it then re-fetches its last row into a slot nobody reads), and
+// the wavefront has no other vector loads in flight while the ring runs.  The fetch cursor runs through the whole queue of the
+// workgroup, so the pipeline does not drain between items.
+__device__ __forceinline__ void load_to_lds_16(const void *gptr, unsigned lds_offset)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_offset) : "memory", "m0");
+}
+// wait until at most N of this wavefront's vector memory loads are in flight (the other counters are left alone)
+template <int N> __device__ __forceinline__ void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "the counter has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <int TS, int K, int H, int NB, bool LOGISTIC>
+__global__ void __launch_bounds__(TS * H)
+partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ y, const float *__restrict__ w,
+                         const DevPiece *__restrict__ pieces, const int32_t *__restrict__ group_item_begin,
+                         const int32_t *__restrict__ item_pieces, float *__restrict__ partial, int d, int nq)
+{
+    constexpr int BT = TS * H, WAVES = TS / 64, LPT = (K + H - 1) / H;     // LPT loads per thread and row; (LPT - 1) * BT < nq always
+    static_assert((NB - 1) * LPT < 64, "the loads in flight per wavefront must fit the hardware counter");
+    static_assert(NB >= 2 && WAVES > 1, "a ring of at least two rows; teams of several wavefronts");
+    const float *X = static_cast<const float *>(Xv);
+    extern __shared__ __align__(16) unsigned char smem[];
+    f4a *ring = reinterpret_cast<f4a *>(smem);                                          // [NB][nq] chunks
+    float *red = reinterpret_cast<float *>(smem + sizeof(f4a) * NB * nq);               // [H][2][WAVES]
+    const unsigned ring_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char *)smem));
+    const int tl = threadIdx.x % TS;
+    const int tib = __builtin_amdgcn_readfirstlane(threadIdx.x / TS);
+    const int wave = tl / 64;
+    const int wgwave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+
+    const int item_begin = group_item_begin[blockIdx.x], item_end = group_item_begin[blockIdx.x + 1];
+
+    // compute role, as in the kernels above: chunks tl, tl + TS, ... of a row; a chunk index past the row reads the row's last chunk
+    // with zero weights (K = ceil(nq / TS), so only a thread's last chunk can lie past the row)
+    float wv[K][4];
+    const int qlast = min(tl + (K - 1) * TS, nq - 1);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int q = k < K - 1 ? tl + k * TS : qlast;
+        const f4u t = *reinterpret_cast<const f4u *>(w + 4 * q);
+        const bool own = tl + k * TS < nq;
+        wv[k][0] = own ? t.x : 0.f; wv[k][1] = own ? t.y : 0.f; wv[k][2] = own ? t.z : 0.f; wv[k][3] = own ? t.w : 0.f;
+    }
+    float acc[K][4];
+#pragma unroll
+    for (int k = 0; k < K; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+    __builtin_amdgcn_s_waitcnt(0);       // the weights are in: from here on the only vector loads of this wavefront are the ring's
+
+    // fetch role: thread t brings chunks t, t + BT, ... of every row.  Only the last of them can lie outside the row, and a whole
+    // wavefront may then have nothing to bring: it skips that load and counts one load fewer per row when it waits.
+    const bool last_any = (LPT - 1) * BT + wgwave * 64 < nq;                 // the same for the whole wavefront
+    const bool last_mine = (LPT - 1) * BT + static_cast<int>(threadIdx.x) < nq;
+
+    // cursors over the workgroup's queue: the fetch cursor runs NB rows ahead of the compute cursor
+    struct Cursor {
+        int item;           // index into the queue; item_end: past the end
+        int rows_left;      // rows of the current item not yet passed
+        int piece;          // compute cursor: this team's piece of the item (-1: none); fetch cursor: unused
+        int64_t row;        // current row of X
+    };
+    auto enter = [&](Cursor &c, bool for_compute) {     // settle on the first item at or after c.item that has pieces
+        for (; c.item < item_end; ++c.item) {
+            int ref = -1, mine = -1;
+#pragma unroll
+            for (int t = 0; t < H; ++t) {
+                const int pi = item_pieces[c.item * H + t];
+                if (pi >= 0) { if (ref < 0) ref = pi; if (t == tib) mine = pi; }
+            }
+            if (ref < 0) continue;                          // a gap in the queue
+            const DevPiece pc = pieces[ref];                // every piece of an item covers the same rows
+            c.row = pc.row_begin;
+            c.rows_left = pc.nrows;
+            c.piece = for_compute ? mine : ref;
+            return;
+        }
+    };
+    Cursor F, C;
+    F.item = C.item = item_begin;
+    F.rows_left = C.rows_left = 0;
+    F.piece = C.piece = -1;
+    F.row = C.row = 0;
+    enter(F, false);
+    enter(C, true);
+    if (C.item >= item_end) return;                        // nothing queued (the same for the whole workgroup)
+
+    // loads of the row under the fetch cursor into ring slot `slot`; then the cursor moves on, staying on its last row once the
+    // queue is exhausted
+    auto issue = [&](int slot) {
+        const float *row = X + F.row * d;
+        const unsigned dst = ring_lds + 16u * static_cast<unsigned>(slot * nq + wgwave * 64);
+#pragma unroll
+        for (int j = 0; j < LPT - 1; ++j) load_to_lds_16(row + 4 * (threadIdx.x + j * BT), dst + 16u * (j * BT));
+        if (last_any) {
+            if (last_mine) load_to_lds_16(row + 4 * (threadIdx.x + (LPT - 1) * BT), dst + 16u * ((LPT - 1) * BT));
+        }
+        if (F.rows_left > 1) { --F.rows_left; ++F.row; }
+        else {
+            Cursor N = F;
+            ++N.item;
+            enter(N, false);
+            if (N.item < item_end) F = N;
+        }
+    };
+    // wait until at most B of this wavefront's rows are still in flight
+    auto wait_for = [&](auto tag) {
+        constexpr int B = decltype(tag)::value;
+        if (last_any) wait_loads<B * LPT>(); else wait_loads<B * (LPT - 1)>();
+    };
+
+#pragma unroll
+    for (int i = 0; i < NB; ++i) issue(i);
+    wait_for(std::integral_constant<int, NB - 1>{});
+    __syncthreads();
+    int slot = 0, par = 0;
+    while (C.item < item_end) {                            // the items of the queue ...
+        const bool active = C.piece >= 0;
+        int64_t row = C.row;
+        for (int left = C.rows_left; left > 0; --left, ++row) {         // ... and the rows of an item
+            float pd = 0.f, yy = 0.f;
+            f4a xr[K];
+            if (active) {
+                yy = y[row];
+#pragma unroll
+                for (int k = 0; k < K; ++k) xr[k] = ring[slot * nq + (k < K - 1 ? tl + k * TS : qlast)];
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < K; ++k) { s = fmaf(xr[k].x, wv[k][0], s); s = fmaf(xr[k].y, wv[k][1], s); s = fmaf(xr[k].z, wv[k][2], s); s = fmaf(xr[k].w, wv[k][3], s); }
+                pd = wave_sum<false>(s);
+                if ((tl & 63) == 0) red[(tib * 2 + par) * WAVES + wave] = pd;
+            }
+            wait_for(std::integral_constant<int, NB - 2>{});      // my part of the next row has landed; the barrier covers the others'
+            __syncthreads();
+            issue(slot);                                         // every team holds this row in registers: its slot is free
+            if (active) {
+                float z = 0.f;
+#pragma unroll
+                for (int i = 0; i < WAVES; ++i) z += red[(tib * 2 + par) * WAVES + i];
+                const float res = (LOGISTIC ? sigmoid(z) : z) - yy;
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    acc[k][0] = fmaf(res, xr[k].x, acc[k][0]); acc[k][1] = fmaf(res, xr[k].y, acc[k][1]);
+                    acc[k][2] = fmaf(res, xr[k].z, acc[k][2]); acc[k][3] = fmaf(res, xr[k].w, acc[k][3]);
+                }
+            }
+            slot = slot + 1 == NB ? 0 : slot + 1;
+            par ^= 1;
+        }
+        if (active) {                                      // the item is done: this team's partial row is complete
+            float *out = partial + static_cast<int64_t>(C.piece) * d;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int q = tl + k * TS;
+                if (q < nq) { f4u t; t.x = acc[k][0]; t.y = acc[k][1]; t.z = acc[k][2]; t.w = acc[k][3]; *reinterpret_cast<f4u *>(out + 4 * q) = t; }
+                acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+            }
+        }
+        ++C.item;
+        enter(C, true);
+    }
+    wait_loads<0>();                      // the re-fetches past the end of the queue land before the workgroup gives its LDS back
+}
+
 // ---- stage 1 for wide rows -----------------------------------------------------------------------------------------
 // When a row is too long for one team's registers the single pass is split in two: first the residuals r = phi(x.w) - y of every
 // row visit (one workgroup per piece, the row streamed in chunks), then G_piece = X^T r per piece and column block.
@@ -739,6 +917,10 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
     {XD, VEC, TS, K, R, H, true,                                                                        \
      {reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, false>),        \
       reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, true>)}}
+#define CR_D(TS, K, NB, H)                                                                             \
+    {0, 4, TS, K, 1, H, true,                                                                          \
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false>),                  \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true>)}, NB}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 const Stage1Variant kVariants[] = {
     // fp32, chunks of 4 columns (4 registers per chunk)
@@ -753,7 +935,10 @@ const Stage1Variant kVariants[] = {
     CR_V(1, 8, 256, 6, 2), CR_V(1, 8, 1024, 2, 2), CR_V(1, 8, 1024, 3, 1),
     // rows shorter than one wide chunk: one column per lane
     CR_V(0, 1, 64, 1, 8), CR_V(1, 1, 64, 1, 8),
-    // fp32 rows staged through LDS.  Eight holders per workgroup, one wavefront each, for rows of up to 1024 chunks ...
+    // fp32 rows of 1537 to 2560 whole 16-byte chunks (up to 40 KB) loaded straight into LDS, ring of four rows: three holders per
+    // workgroup (768 threads).  Listed before the register-staged kernels of two holders that cover the same widths.
+    CR_D(256, 7, 4, 3), CR_D(256, 8, 4, 3), CR_D(256, 9, 4, 3), CR_D(256, 10, 4, 3),
+    // fp32 rows staged through LDS by way of registers (any width).  Eight holders per workgroup, one wavefront each, for rows of up to 1024 chunks ...
     CR_S(0, 4, 64, 5, 1, 8), CR_S(0, 4, 64, 6, 1, 8), CR_S(0, 4, 64, 7, 1, 8), CR_S(0, 4, 64, 8, 1, 8), CR_S(0, 4, 64, 9, 1, 8),
     CR_S(0, 4, 64, 10, 1, 8), CR_S(0, 4, 64, 11, 1, 8), CR_S(0, 4, 64, 12, 1, 8), CR_S(0, 4, 64, 13, 1, 8), CR_S(0, 4, 64, 14, 1, 8),
     CR_S(0, 4, 64, 15, 1, 8), CR_S(0, 4, 64, 16, 1, 8),
@@ -774,9 +959,13 @@ int stage1_chunk_width(int x_dtype, int64_t d)
 
 }  // namespace
 
-size_t Stage1Variant::lds_bytes() const
+size_t Stage1Variant::lds_bytes(int64_t d) const
 {
     if (!staged) return 0;
+    if (ring > 0) {        // ring of whole rows, then the partial dot products of the teams' wavefronts
+        const size_t nq = static_cast<size_t>((d + vec - 1) / vec);
+        return 16 * static_cast<size_t>(ring) * nq + sizeof(float) * tpb * 2 * (team_size / 64);
+    }
     const size_t row_chunks = static_cast<size_t>((k + tpb - 1) / tpb) * block();
     return 16 * 2 * rows * row_chunks + sizeof(float) * tpb * 2 * rows * (team_size / 64);
 }
@@ -798,19 +987,23 @@ const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_ho
 {
     const int vec = stage1_chunk_width(x_dtype, d);
     const int64_t nq = (d + vec - 1) / vec;
-    // the table lists workgroups of 8, then 4, then 2 holders: the first that is not wider than the rows need (3 holders still
-    // fill a workgroup of 4 better than two of 2; 5 and more take 8)
+    // the widest workgroup that is not wider than the rows need: 8 holders for rows with 5 or more, 4 (3 for long rows) for 3 or 4,
+    // else 2.  The table lists wide workgroups before narrow ones; the kernel that loads straight into LDS needs rows of whole
+    // 16-byte chunks and a ring that fits LDS at this width.
     const int widest = max_holders >= 5 ? 8 : max_holders >= 3 ? 4 : 2;
-    for (const Stage1Variant &v : kVariants)
-        if (v.staged && v.xd == x_dtype && v.vec == vec && v.k == (nq + v.team_size - 1) / v.team_size && v.tpb <= widest) return &v;
+    for (const Stage1Variant &v : kVariants) {
+        if (!v.staged || v.xd != x_dtype || v.vec != vec || v.k != (nq + v.team_size - 1) / v.team_size || v.tpb > widest) continue;
+        if (v.ring > 0 && (d % vec != 0 || v.lds_bytes(d) > kLdsPerWorkgroup)) continue;
+        return &v;
+    }
     return nullptr;
 }
 
-hipError_t prepare_stage1(const Stage1Variant &v)
+hipError_t prepare_stage1(const Stage1Variant &v, int64_t d)
 {
-    if (v.lds_bytes() <= 48 * 1024) return hipSuccess;
+    if (v.lds_bytes(d) <= 48 * 1024) return hipSuccess;
     for (const void *fn : v.fn) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(v.lds_bytes()));
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(v.lds_bytes(d)));
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -836,7 +1029,7 @@ hipError_t launch_partial_grads_staged(const Stage1Variant &v, const void *X, co
     int nq = static_cast<int>((d + v.vec - 1) / v.vec);
     void *args[] = {&X, &y, &w, &pieces, &group_item_begin, &item_pieces, &partial, &di, &nq};
     dim3 grid(num_groups), block(v.block());
-    return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, v.lds_bytes(), stream);
+    return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, v.lds_bytes(d), stream);
 }
 
 namespace {

@@ -118,7 +118,11 @@ CASES = [
     ("cr-12x2-s2", 2, 12, 2, 15_611, 1_000, cr.CR_LINEAR, cr.CR_F32, None),       # ... 2 per group
     ("cr-12x2-s5", 2, 12, 5, 49_920, 432, cr.CR_LOGISTIC, cr.CR_F32, None),       # ... 5 per group (resiliency 5/12, 49 920 points as in the network experiment): 36 holders per row
     # rows staged through LDS and shared by the holders in one workgroup
-    ("staged-2-holders", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # 10 chunks per thread, odd and even step counts
+    ("direct-3-holders", 2, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # rows loaded straight into LDS, 10 chunks per thread, cells of 2, 3 and 4 holders
+    ("direct-3-holders-k8", 2, 3, 1, 2_501, 8_192, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 3)),    # 2048 chunks: no partial wavefront in the fetch; cells shorter than the ring
+    ("direct-3-holders-k9", 1, 6, 2, 2_000, 8_196, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 1)),      # single-row cells: the ring runs across items; last fetch wavefronts idle
+    ("direct-default", 2, 4, 1, 70_000, 6_400, cr.CR_LINEAR, cr.CR_F32, None),                                  # large enough for the default split to pick it
+    ("staged-2-holders", 1, 4, 1, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # two holders per row: register-staged kernel, 10 chunks per thread
     ("staged-2-holders-odd-d", 2, 4, 1, 2_003, 9_999, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 64)),
     ("staged-4-holders", 2, 4, 1, 5_003, 2_052, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 50)),       # four 256-thread teams, two rows per step
     ("staged-4-holders-k6", 2, 3, 1, 2_000, 5_640, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 90)),
