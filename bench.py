@@ -2,13 +2,21 @@
 """Benchmark of the CodedReduce hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
-host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> cr_gd_update
+host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> gradient step
 (issued through cr_gd_run, which enqueues these steps for every mask; the gradient step rides in the decode launch).
-Prints ONE JSON line: iterations/s, the roofline of the dominant kernel (measured live with HIP events on the
-library's stream, over the timed steps) and the CPU oracle timed on a bounded sample of the same workload.  The other
-kernels' averages come from a few more steps after the timed region ("timed_region": false in the "kernels" table).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+Prints ONE JSON line.  Its top level is the headline workload (configuration 5: the largest, end-to-end iterations/s);
+"configs" holds the same record for every benchmark configuration and for the comparison workloads of the paper's
+computation-load discussion, all measured in this run: iterations/s, the roofline of the dominant kernel (timed live
+with HIP events on the library's stream over the timed steps: average, minimum, median, maximum), the CPU oracle
+timed on a bounded sample of the same workload, and the parity of one GPU iteration with that oracle.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+roofline.frac is the fraction of the resource that binds: for the memory-bound kernels the bytes HBM really moved per
+launch (rocprofv3 FETCH_SIZE + WRITE_SIZE of the same kernel and work split, profiles/hbm_traffic.json) over the
+kernel's time, against 8 TB/s; the algorithmic bytes (every holder's read of a row charged) are reported beside it as
+algorithmic_GBps / algorithmic_ratio and exceed the peak where holders share one fetch.
 """
 from __future__ import annotations
 
@@ -23,8 +31,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E bandwidth
-FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X, published (packed fp32); 78.6 without packed instructions
+HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E bandwidth
+FP32_VECTOR_PEAK_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop; the published 157.3 counts packed instructions
 KERNEL_NAMES = ["partial_grads", "reduce_pieces", "encode", "decode", "update"]
 DESCRIPTIONS = {
     "cfg1": "CR tree L=2 n=3 s=1, linear regression fp32, m=1200 d=100",
@@ -35,26 +43,42 @@ DESCRIPTIONS = {
     "gc20": "one-layer gradient coding, n=20 s=4 (same data and resiliency as cfg2), linear regression fp32, m=100000 d=10000",
     "umw20": "uncoded master-worker, n=20 s=0 (same data as cfg2), linear regression fp32, m=100000 d=10000",
     "paper84": "the paper's linear-regression experiment: CR tree L=3 n=4 s=1 (84 workers), fp32, m=7644 d=6500, noise N(0,1)",
-    "nn12": "aggregation only: CR tree L=2 n=12 s=3 (156 workers), fp32 partition-gradient vectors of length 117706 (network sized), encode+decode",
+    "nn12": "aggregation only: CR tree L=2 n=12 s=5 (156 workers, resiliency 5/12), fp32 partition-gradient vectors of length 117706 (network sized), encode+decode",
 }
+HEADLINE = "cfg5"
+DEFAULT_SET = ["cfg5", "cfg2", "gc20", "umw20", "cfg3", "cfg4", "cfg1", "nn12", "paper84"]     # cfg2, gc20, umw20 share one data set
 
 
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def load_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (None if not measured)."""
+def split_signature(info) -> str:
+    """What identifies the kernel and work split a traffic record belongs to."""
+    kind = ["equal_ranges", "row_cells", "shared_cells"][info.split_kind] if info.split_kind >= 0 else "none"
+    return f"{kind}:{info.split_value}:team{info.stage1_team_size}x{info.stage1_teams_per_group}:staged{info.stage1_staged}"
+
+
+def load_traffic(workload: str, signature: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if it was taken with this kernel
+    and work split (else None and the reason)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
-        return None
+        return None, "no traffic record"
     with open(path) as f:
-        table = json.load(f)
-    entry = table.get(workload)
-    return None if entry is None else entry.get("bytes_per_launch")
+        entry = json.load(f).get(workload)
+    if entry is None:
+        return None, "no traffic record for this workload"
+    if entry.get("split_signature") not in (None, signature):
+        return None, f"traffic record is for {entry.get('split_signature')}, this run uses {signature}"
+    return entry.get("bytes_per_launch"), entry.get("source")
 
 
-def cpu_baseline(cfg, data, plan_B, w_host, mask, g_gpu, budget_s: float):
+def stats(ms: np.ndarray) -> dict:
+    return {"avg": float(ms.mean()), "min": float(ms.min()), "median": float(np.median(ms)), "max": float(ms.max())}
+
+
+def cpu_baseline_regression(cfg, data, w_host, mask, g_gpu, budget_s: float):
     """The oracle as it stands: the CR tree literally (every holder visits its own rows) in fp64 on the host cores."""
     from oracle import cr_tree, gc_code, native
 
@@ -87,51 +111,56 @@ def cpu_baseline(cfg, data, plan_B, w_host, mask, g_gpu, budget_s: float):
             "seconds": elapsed}, parity
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
-    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of oracle work for the CPU baseline (0 = skip)")
-    ap.add_argument("--teams", type=int, default=0, help="stage-1 split: this many equal contiguous ranges")
-    ap.add_argument("--cell-rows", type=int, default=0, help="stage-1 split: row cells of this many rows")
-    ap.add_argument("--shared-rows", type=int, default=0, help="stage-1 split: cells of at most this many rows shared through LDS")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="run only a plain 1 GiB elementwise copy kernel a few times (reference for rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        return 2
+def cpu_baseline_aggregation(cfg, slabs_host_cols, cols, mask, g_gpu_cols, d):
+    """The oracle's tree execution (numpy fp64, one thread) on a sample of columns of the caller-supplied slab gradients."""
+    from oracle import cr_tree, gc_code
 
+    L, n, s = cfg["L"], cfg["n"], cfg["s"]
+    B = gc_code.design_code(n, s, L, 190201981)[0]
+    own, _ = cr_tree.cr_allocate(L, n, s, cfg["m"], B)
+    slabs = cr_tree.slabs_of(own)
+    t0 = time.perf_counter()
+    ng = [np.zeros(len(cols)) for _ in own]
+    for q, (node, _, _, c) in enumerate(slabs):
+        ng[node] += float(c) * slabs_host_cols[q].astype(np.float64)
+    rows = {}
+    _, g = cr_tree.cr_execute(L, n, s, ng, mask, lambda T: rows.setdefault(T, gc_code.decoding_row(B, T)))
+    elapsed = time.perf_counter() - t0
+    parity = float(np.linalg.norm(g_gpu_cols - g) / np.linalg.norm(g))
+    return {"value": (len(cols) / d) / elapsed, "unit": "iterations/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(cols)} of {d} columns of one encode+decode (all {len(slabs)} slabs, every message), scaled to one iteration",
+            "seconds": elapsed}, parity
+
+
+_DATA_CACHE = {}
+
+
+def dataset(cfg, wl):
+    key = (cfg["seed"], cfg["m"], cfg["d"], cfg["x_dtype"], cfg["model"], cfg["noise"], cfg["w0_std"])
+    if key not in _DATA_CACHE:
+        _DATA_CACHE.clear()                             # one data set in host memory at a time
+        _DATA_CACHE[key] = wl.make_dataset(cfg, threads=min(16, os.cpu_count() or 8))
+    return _DATA_CACHE[key]
+
+
+def run_workload(name: str, steps: int, warmup: int, cpu_budget: float, args) -> dict:
     import torch
 
     import paper_1902_01981_amd as cr
     from cr_inputs import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 1
-    if args.calibrate:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            torch.mul(src, 1.0, out=dst)                 # reads 2^30 bytes, writes 2^30 bytes per launch
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate": "torch.mul(src, 1.0, out=dst)", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 5}))
-        return 0
-    cr.load_library()
-    cfg = wl.config(args.workload)
+    cfg = wl.config(name)
     L, n, s, m, d = cfg["L"], cfg["n"], cfg["s"], cfg["m"], cfg["d"]
     aggregate = cfg["model"] == wl.AGGREGATE_ONLY
     t0 = time.perf_counter()
     plan = cr.cr_plan_ex(L, n, s, m, d, model=cfg["model"], x_dtype=cfg["x_dtype"])
-    if args.teams and not aggregate:
-        cr.cr_plan_set_split(plan, cr.CR_SPLIT_EQUAL_RANGES, args.teams)
-    elif args.cell_rows and not aggregate:
-        cr.cr_plan_set_split(plan, cr.CR_SPLIT_ROW_CELLS, args.cell_rows)
-    elif args.shared_rows and not aggregate:
-        cr.cr_plan_set_split(plan, cr.CR_SPLIT_SHARED_CELLS, args.shared_rows)
+    if not aggregate:
+        if args.teams:
+            cr.cr_plan_set_split(plan, cr.CR_SPLIT_EQUAL_RANGES, args.teams)
+        elif args.cell_rows:
+            cr.cr_plan_set_split(plan, cr.CR_SPLIT_ROW_CELLS, args.cell_rows)
+        elif args.shared_rows:
+            cr.cr_plan_set_split(plan, cr.CR_SPLIT_SHARED_CELLS, args.shared_rows)
 
     # ---- inputs, generated on the host from the seed and moved to HBM before any timing
     data = None
@@ -149,129 +178,238 @@ def main() -> int:
         del atoms_dev
         w_dev = torch.zeros(d, dtype=torch.float32, device="cuda")
     else:
-        data = wl.make_dataset(cfg, threads=min(16, os.cpu_count() or 8))
+        data = dataset(cfg, wl)
         X = data["X"]
         X_dev = torch.from_numpy(X.view(np.int16) if X.dtype == np.uint16 else X).cuda()
         y_dev = torch.from_numpy(data["y"]).cuda()
         w_dev = torch.from_numpy(data["w0"]).cuda()
-    log(f"inputs ready in {time.perf_counter() - t0:.1f}s")
+    log(f"{name}: inputs ready in {time.perf_counter() - t0:.1f}s")
     ws = cr.Workspace(plan)
     info = ws.info
     g_dev = torch.empty(d, dtype=torch.float32, device="cuda")
     rng = wl.mask_stream(cfg)
     lr = float(cfg["lr"])
 
-    def run(steps):
-        # host-drawn straggler masks, then the whole path; for regression workloads the gradient-descent loop is a library call
-        # that enqueues its steps without waiting for the device, so the masks of the next batch are drawn while this one runs
-        done = 0
-        while done < steps:
-            batch = min(8, steps - done)
-            masks = np.stack([wl.draw_mask(rng, L, n, s) for _ in range(batch)])
-            if aggregate:
-                for mask in masks:
-                    cr.cr_load_partial_grads(plan, G_dev)
-                    cr.cr_encode_tree(plan, mask)
-                    cr.cr_decode_root(plan, g_dev)
-            else:
-                cr.cr_gd_run(plan, X_dev, y_dev, w_dev, g_dev, masks, lr)
-            done += batch
+    def draw(count):
+        return np.stack([wl.draw_mask(rng, L, n, s) for _ in range(count)])
+
+    def run(masks):
+        # the whole path for every host-drawn straggler mask; for regression workloads the gradient-descent loop is one library
+        # call per batch of masks, which enqueues its steps without waiting for the device
+        if aggregate:
+            for mask in masks:
+                cr.cr_load_partial_grads(plan, G_dev)
+                cr.cr_encode_tree(plan, mask)
+                cr.cr_decode_root(plan, g_dev)
+        else:
+            for lo in range(0, len(masks), 8):
+                cr.cr_gd_run(plan, X_dev, y_dev, w_dev, g_dev, masks[lo:lo + 8], lr)
 
     dominant = "encode" if aggregate else "partial_grads"
+    dom_id = KERNEL_NAMES.index(dominant)
 
     def read_kernels(into):
-        for kid, name in enumerate(KERNEL_NAMES):
+        for kid, kname in enumerate(KERNEL_NAMES):
             ms, launches, nbytes = cr.cr_profile_read(plan, kid)
             if launches:
-                into[name] = {"avg_ms": ms / launches, "launches": launches, "algorithmic_bytes_per_launch": nbytes // launches,
-                              "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None}
+                into[kname] = {"ms": stats(cr.cr_profile_samples(plan, kid)), "launches": launches,
+                               "algorithmic_bytes_per_launch": nbytes // launches,
+                               "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None}
 
-    run(args.warmup)
+    # Clock ramp, untimed and before the warm-up steps: after the idle stretch in which the inputs were generated the device
+    # takes about 10 ms of continuous load to reach its running clocks (the first launches of a burst run up to 40 % slower,
+    # see the per-launch samples), so the path is run until it has kept the device busy for RAMP_MS.  Then the W warm-up steps,
+    # the synchronisation, and exactly K timed steps whose masks are already drawn (no host work between the two).
+    ramp_steps = 0
+    probe_masks = draw(4)
+    t_r = time.perf_counter()
+    run(probe_masks)
+    torch.cuda.synchronize()
+    per_step = max((time.perf_counter() - t_r) / 4, 1e-6)
+    ramp_steps = int(min(2000, max(0, args.ramp_ms * 1e-3 / per_step)))
+    if ramp_steps:
+        run(draw(ramp_steps))
+    run(draw(warmup))
+    timed_masks = draw(steps)
+    extra_masks = draw(min(steps, 10))
     torch.cuda.synchronize()
     # timed region: only the dominant kernel is bracketed by events (every bracket costs a few microseconds of device time)
-    cr.cr_profile_enable(plan, 1 << KERNEL_NAMES.index(dominant))
+    cr.cr_profile_enable(plan, 1 << dom_id)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    run(args.steps)
+    run(timed_masks)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     kernels = {}
     read_kernels(kernels)
     # the other kernels, from a few more steps outside the timed region with every launch bracketed
     cr.cr_profile_enable(plan, True)
-    run(min(args.steps, 10))
+    run(extra_masks)
     others = {}
     read_kernels(others)
-    for name, entry in others.items():
-        kernels.setdefault(name, dict(entry, timed_region=False))
+    for kname, entry in others.items():
+        kernels.setdefault(kname, dict(entry, timed_region=False))
     cr.cr_profile_enable(plan, False)
     dk = kernels[dominant]
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["algorithmic_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS, "traffic": load_traffic(args.workload),
-                "avg_kernel_ms": dk["avg_ms"], "algorithmic_bytes_per_launch": dk["algorithmic_bytes_per_launch"]}
+    avg_s = dk["ms"]["avg"] * 1e-3
+    signature = split_signature(info) if not aggregate else "encode"
+    traffic, traffic_source = load_traffic(name, signature)
     # yardstick: what a plain streaming read of the same buffer reaches on this device right now
     big = G_dev if aggregate else X_dev
     sink = torch.empty(16384, dtype=torch.float32, device="cuda")
     nbytes = min(big.numel() * big.element_size(), 4 << 30) // 16 * 16
-    roofline["stream_read_GBps"] = cr.cr_probe_read_bandwidth(big, nbytes, sink, 10, torch.cuda.current_stream().cuda_stream)
-    if roofline["traffic"]:
-        # what HBM really moved (rocprofv3 counters of an earlier run of this workload), as a rate over this run's kernel time
-        roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9
-        roofline["traffic_frac_of_stream_read"] = roofline["traffic_GBps"] / roofline["stream_read_GBps"]
+    stream_gbps = cr.cr_probe_read_bandwidth(big, nbytes, sink, 10, torch.cuda.current_stream().cuda_stream) if nbytes >= (1 << 20) else None
+    traffic_gbps = traffic / avg_s / 1e9 if traffic else None
+    hbm = {"traffic": traffic, "traffic_source": traffic_source, "traffic_GBps": traffic_gbps,
+           "traffic_frac_of_peak": traffic_gbps / HBM_PEAK_GBPS if traffic else None,
+           "frac_of_stream_read": traffic_gbps / stream_gbps if traffic and stream_gbps else None,
+           "traffic_frac_whole_step": traffic / (elapsed / steps) / 1e9 / HBM_PEAK_GBPS if traffic else None,
+           "stream_read_GBps": stream_gbps}
+    common = {"kernel": dominant, "kernel_ms": dk["ms"], "algorithmic_bytes_per_launch": dk["algorithmic_bytes_per_launch"],
+              "algorithmic_GBps": dk["algorithmic_GBps"], "algorithmic_ratio": dk["algorithmic_GBps"] / HBM_PEAK_GBPS}
     if not aggregate and cfg["x_dtype"] == wl.BF16:
-        # bf16 rows: stage 1 is bound by vector-ALU issue (a widening operation and two multiply-adds per element), not by memory;
-        # 4 flop per element of X visited against the chip's fp32 vector peak (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop,
-        # x 2 with packed instructions, which this build does not use)
+        # bf16 rows: stage 1 is bound by vector-ALU issue (a widening operation and two multiply-adds per element), not by memory:
+        # 4 flop per element of X visited, against the vector peak of the instructions this build issues
         flops = 4.0 * info.row_visits * d
-        achieved = flops / (dk["avg_ms"] * 1e-3) / 1e12
-        roofline = dict(roofline, bound="alu", achieved=achieved, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=achieved / FP32_VECTOR_PEAK_TFLOPS, flops_per_launch=flops,
-                        hbm_view={"achieved_GBps": dk["algorithmic_GBps"], "frac": dk["algorithmic_GBps"] / HBM_PEAK_GBPS})
+        achieved = flops / avg_s / 1e12
+        roofline = dict(common, bound="alu", achieved=achieved, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / FP32_VECTOR_PEAK_TFLOPS, traffic=traffic, flops_per_launch=flops,
+                        peak_derivation="256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop per multiply-add = 78.6 TFLOP/s; "
+                                        "the published 157.3 TFLOP/s counts packed fp32 instructions, which this build does not issue",
+                        hbm_view=hbm)
+    else:
+        roofline = dict(common, bound="hbm", achieved=traffic_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
+                        frac=traffic_gbps / HBM_PEAK_GBPS if traffic else None, **hbm)
 
     # ---- CPU baseline: the oracle on the host cores, same inputs, bounded; also a parity check of one more GPU iteration
     baseline, parity = None, None
-    if args.cpu_budget > 0 and not aggregate:
-        # at the starting model: after many steps w sits at the optimum, where the gradient is the difference of large
-        # cancelling terms and a relative error says nothing
+    if cpu_budget > 0:
         mask = wl.draw_mask(rng, L, n, s)
-        w_host = data["w0"]
-        w_dev.copy_(torch.from_numpy(w_host))
-        cr.cr_partial_grads(plan, X_dev, y_dev, w_dev)
-        cr.cr_encode_tree(plan, mask)
-        cr.cr_decode_root(plan, g_dev)
-        cr.cr_synchronize(plan)
-        baseline, parity = cpu_baseline(cfg, data, None, w_host, mask, g_dev.cpu().numpy().astype(np.float64), args.cpu_budget)
-        log(f"cpu baseline: {baseline}")
+        if aggregate:
+            ncols = int(min(d, max(4096, (1 << 18) * cpu_budget / 20.0))) // 4 * 4
+            cols = np.arange(ncols) + ((d - ncols) // 2) // 4 * 4          # a block in the middle of the vectors
+            cr.cr_load_partial_grads(plan, G_dev)
+            cr.cr_encode_tree(plan, mask)
+            cr.cr_decode_root(plan, g_dev)
+            cr.cr_synchronize(plan)
+            baseline, parity = cpu_baseline_aggregation(cfg, G_dev[:, cols[0]:cols[-1] + 1].cpu().numpy(), cols, mask,
+                                                        g_dev[cols[0]:cols[-1] + 1].cpu().numpy().astype(np.float64), d)
+        else:
+            # at the starting model: after many steps w sits at the optimum, where the gradient is the difference of large
+            # cancelling terms and a relative error says nothing
+            w_host = data["w0"]
+            w_dev.copy_(torch.from_numpy(w_host))
+            cr.cr_partial_grads(plan, X_dev, y_dev, w_dev)
+            cr.cr_encode_tree(plan, mask)
+            cr.cr_decode_root(plan, g_dev)
+            cr.cr_synchronize(plan)
+            baseline, parity = cpu_baseline_regression(cfg, data, w_host, mask, g_dev.cpu().numpy().astype(np.float64), cpu_budget)
+        log(f"{name}: cpu baseline {baseline}, parity {parity}")
 
-    total_bytes = sum(k["algorithmic_bytes_per_launch"] for k in kernels.values())
     out = {
-        "metric": "CR gradient iterations/sec",
-        "value": args.steps / elapsed,
+        "workload": f"{name}: {DESCRIPTIONS[name]}",
+        "value": steps / elapsed,
         "unit": "iterations/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
+        "steps": steps,
+        "warmup": warmup,
+        "clock_ramp_steps": ramp_steps + 4,
+        "ms_per_step": elapsed / steps * 1e3,
+        "us_per_iteration": elapsed / steps * 1e6,
         "dtype": "bf16" if cfg["x_dtype"] == wl.BF16 else "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {DESCRIPTIONS[args.workload]}", "L": L, "n": n, "s": s, "m": m, "d": d,
+        "config": {"workload": f"{name}: {DESCRIPTIONS[name]}", "L": L, "n": n, "s": s, "m": m, "d": d,
                    "workers": info.num_workers, "slabs": info.num_slabs, "row_visits": info.row_visits,
+                   "computation_load": info.r_cr, "rows_per_worker": [info.min_rows, info.max_rows],
                    "stage1_teams": info.num_teams, "stage1_pieces": info.num_pieces, "code_gamma": info.gamma,
                    "stage1_split": ["equal_ranges", "row_cells", "shared_cells"][info.split_kind] if info.split_kind >= 0 else None,
                    "stage1_split_value": info.split_value, "stage1_team_size": info.stage1_team_size,
-                   "stage1_holders_per_workgroup": info.stage1_teams_per_group if info.stage1_staged else 1},
-        "algorithmic_GBps_whole_step": total_bytes / (elapsed / args.steps) / 1e9,
-        "hbm_frac_whole_step": total_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+                   "stage1_holders_per_workgroup": info.stage1_teams_per_group if info.stage1_staged else 1,
+                   "l2_domains": info.l2_domains, "l2_sharing_checked": info.l2_sharing},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": baseline,
         "parity_rel_l2_vs_oracle": parity,
     }
-    print(json.dumps(out), flush=True)
     cr.cr_plan_destroy(plan)
+    del ws, big
+    if aggregate:
+        del G_dev
+    else:
+        del X_dev, y_dev
+    torch.cuda.empty_cache()
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, choices=sorted(DESCRIPTIONS),
+                    help="run this workload only (default: configuration 5 as the headline and every other one under 'configs')")
+    ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle work per workload for the CPU baseline (0 = skip)")
+    ap.add_argument("--ramp-ms", type=float, default=60.0,
+                    help="untimed load before the warm-up steps, in milliseconds of device time, to bring the clocks up (0 = none)")
+    ap.add_argument("--teams", type=int, default=0, help="stage-1 split: this many equal contiguous ranges")
+    ap.add_argument("--cell-rows", type=int, default=0, help="stage-1 split: row cells of this many rows")
+    ap.add_argument("--shared-rows", type=int, default=0, help="stage-1 split: cells of at most this many rows shared through LDS")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run only a plain 1 GiB elementwise copy kernel a few times (reference for rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_1902_01981_amd as cr
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    if args.calibrate:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)                 # reads 2^30 bytes, writes 2^30 bytes per launch
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "torch.mul(src, 1.0, out=dst)", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 5}))
+        return 0
+    cr.load_library()
+    names = [args.workload] if args.workload else DEFAULT_SET
+    records = {}
+    for name in names:
+        records[name] = run_workload(name, args.steps, args.warmup, args.cpu_budget, args)
+        log(f"{name}: {records[name]['value']:.1f} it/s, dominant kernel {records[name]['roofline']['kernel_ms']}")
+    head = records[names[0]]
+    out = {
+        "metric": "CR gradient iterations/sec",
+        "value": head["value"],
+        "unit": "iterations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head["dtype"],
+        "data": "synthetic",
+        "config": head["config"],
+        "roofline": head["roofline"],
+        "kernels": head["kernels"],
+        "cpu_baseline": head["cpu_baseline"],
+        "parity_rel_l2_vs_oracle": head["parity_rel_l2_vs_oracle"],
+    }
+    if len(names) > 1:
+        out["configs"] = {k: v for k, v in records.items()}
+        # Section III-C's comparison of computation loads on configuration 2's data (20 workers, one straggler in four tolerated)
+        out["computation_load_comparison"] = {
+            k: {"scheme": label, "load_r": records[k]["config"]["computation_load"], "iterations_per_s": records[k]["value"],
+                "stage1_ms": records[k]["roofline"]["kernel_ms"]["avg"], "algorithmic_bytes_per_launch": records[k]["roofline"]["algorithmic_bytes_per_launch"],
+                "traffic_frac_of_peak": records[k]["roofline"].get("traffic_frac_of_peak")}
+            for k, label in (("umw20", "uncoded master-worker, r = 1/N"), ("cfg2", "CodedReduce (4,2) tree, r = r_CR"), ("gc20", "gradient coding, r = (S+1)/N"))
+            if k in records}
+    print(json.dumps(out), flush=True)
     return 0
 
 

@@ -27,9 +27,9 @@ CONFIGS = {
     "cfg2": dict(L=2, n=4, s=1, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),
     "cfg3": dict(L=3, n=4, s=1, m=252_000, d=4_096, model=LOGISTIC, x_dtype=F32, noise=0.1, steps=20, lr=1e-5, w0_std=None),
     "cfg4": dict(L=2, n=8, s=2, m=88, d=1 << 24, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
-    # the paper's simulated network training: (12,2) tree, 156 workers, about 120 000 parameters (5 layers: 3x16x3x3, 16x64x4x4,
-    # 64x384, 384x192, 192x10 weights plus biases = 117 706), aggregation only
-    "nn12": dict(L=2, n=12, s=3, m=156 * 40, d=117_706, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
+    # the paper's simulated network training: (12,2) tree, 156 workers, resiliency 5/12, 49 920 data points, about 120 000 parameters
+    # (5 layers: 3x16x3x3, 16x64x4x4, 64x384, 384x192, 192x10 weights plus biases = 117 706), aggregation only
+    "nn12": dict(L=2, n=12, s=5, m=49_920, d=117_706, model=AGGREGATE_ONLY, x_dtype=F32, noise=0.0, steps=20, lr=0.0, w0_std=1.0),
     # configuration 2's data with 20 workers under one master instead of a (4,2) tree: gradient coding with the same resiliency
     # (4 of 20 = 1 of 4 children may straggle) and the uncoded split.  Section III-C compares their computation loads.
     "gc20": dict(L=1, n=20, s=4, m=100_000, d=10_000, model=LINEAR, x_dtype=F32, noise=0.01, steps=50, lr=1e-6, w0_std=1.0),

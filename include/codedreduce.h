@@ -225,6 +225,10 @@ int cr_get_messages(const cr_plan_t *plan, const float **M_dev);   /* N x d, row
 #define CR_PROFILE_ALL ((1 << CR_K_COUNT) - 1)
 int cr_profile_enable(cr_plan_t *plan, int kernels);
 int cr_profile_read(cr_plan_t *plan, int kernel, double *total_ms, int64_t *launches, int64_t *algorithmic_bytes);
+/* the duration in milliseconds of every single timed launch of one kernel id since the last non-zero cr_profile_enable, in launch
+ * order (the first 65536 of them): up to `capacity` values are copied to ms (host), *count receives how many there are; waits for
+ * the stream like cr_profile_read */
+int cr_profile_samples(cr_plan_t *plan, int kernel, float *ms, int64_t capacity, int64_t *count);
 /* algorithmic bytes of the most recent launch of a kernel id (0 if none yet) */
 int cr_last_algorithmic_bytes(const cr_plan_t *plan, int kernel, int64_t *bytes);
 int cr_synchronize(cr_plan_t *plan); /* wait for the bound stream */

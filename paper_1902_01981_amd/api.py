@@ -28,7 +28,7 @@ EXPORTS = [
     "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
-    "cr_probe_read_bandwidth", "cr_aggregate_static",
+    "cr_probe_read_bandwidth", "cr_aggregate_static", "cr_profile_samples",
 ]
 
 
@@ -85,6 +85,7 @@ def load_library():
         lib.cr_get_messages.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_profile_enable.argtypes = [vp, c_int]
         lib.cr_profile_read.argtypes = [vp, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        lib.cr_profile_samples.argtypes = [vp, c_int, vp, i64, ctypes.POINTER(i64)]
         lib.cr_last_algorithmic_bytes.argtypes = [vp, c_int, ctypes.POINTER(i64)]
         lib.cr_synchronize.argtypes = [vp]
         lib.cr_probe_read_bandwidth.argtypes = [vp, ctypes.c_size_t, vp, c_int, vp, ctypes.POINTER(ctypes.c_double)]
@@ -310,6 +311,16 @@ def cr_profile_read(plan: int, kernel: int):
     ms, n, b = ctypes.c_double(), ctypes.c_int64(), ctypes.c_int64()
     _check(load_library().cr_profile_read(plan, kernel, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(b)))
     return ms.value, n.value, b.value
+
+
+def cr_profile_samples(plan: int, kernel: int) -> np.ndarray:
+    """Milliseconds of every timed launch of one kernel id since profiling was last switched on."""
+    n = ctypes.c_int64()
+    _check(load_library().cr_profile_samples(plan, kernel, 0, 0, ctypes.byref(n)))
+    out = np.empty(n.value, dtype=np.float32)
+    if n.value:
+        _check(load_library().cr_profile_samples(plan, kernel, out.ctypes.data, n.value, ctypes.byref(n)))
+    return out
 
 
 def cr_last_algorithmic_bytes(plan: int, kernel: int) -> int:

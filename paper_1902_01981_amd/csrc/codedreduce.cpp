@@ -41,6 +41,7 @@ int hip_fail(hipError_t e, const char *what)
 
 constexpr uint64_t kDefaultSeed = 190201981ull;
 constexpr int kStagingSlots = 4;
+constexpr size_t kMaxSamples = size_t(1) << 16;
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -105,6 +106,7 @@ struct cr_plan_s {
     std::vector<hipEvent_t> event_pool;
     double total_ms[CR_K_COUNT] = {};
     int64_t launches[CR_K_COUNT] = {}, bytes_sum[CR_K_COUNT] = {}, bytes_last[CR_K_COUNT] = {};
+    std::vector<float> samples[CR_K_COUNT];         // duration of every timed launch since the totals were last cleared (bounded)
 };
 
 namespace {
@@ -330,6 +332,7 @@ int fold_timings(cr_plan_t *p)
         CR_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
         p->total_ms[t.kernel] += ms;
         p->launches[t.kernel] += 1;
+        if (p->samples[t.kernel].size() < kMaxSamples) p->samples[t.kernel].push_back(ms);
         p->event_pool.push_back(t.start);
         p->event_pool.push_back(t.stop);
     }
@@ -909,7 +912,7 @@ int cr_profile_enable(cr_plan_t *p, int kernels)
     }
     if (kernels < 0 || kernels > CR_PROFILE_ALL) return fail(CR_E_INVAL, "kernel mask out of range");
     if (kernels) {                                      // a new selection starts new totals
-        for (int k = 0; k < CR_K_COUNT; ++k) { p->total_ms[k] = 0.0; p->launches[k] = 0; p->bytes_sum[k] = 0; }
+        for (int k = 0; k < CR_K_COUNT; ++k) { p->total_ms[k] = 0.0; p->launches[k] = 0; p->bytes_sum[k] = 0; p->samples[k].clear(); }
     }
     p->profiling = static_cast<unsigned>(kernels);
     return CR_OK;
@@ -926,6 +929,21 @@ int cr_profile_read(cr_plan_t *p, int kernel, double *total_ms, int64_t *launche
     if (total_ms) *total_ms = p->total_ms[kernel];
     if (launches) *launches = p->launches[kernel];
     if (algorithmic_bytes) *algorithmic_bytes = p->bytes_sum[kernel];
+    return CR_OK;
+}
+
+int cr_profile_samples(cr_plan_t *p, int kernel, float *ms, int64_t capacity, int64_t *count)
+{
+    if (!p || !count || kernel < 0 || kernel >= CR_K_COUNT || capacity < 0 || (capacity > 0 && !ms)) return fail(CR_E_INVAL, "bad argument");
+    if (p->bound) {
+        CR_HIP(hipStreamSynchronize(p->stream));
+        int rc = fold_timings(p);
+        if (rc != CR_OK) return rc;
+    }
+    const std::vector<float> &v = p->samples[kernel];
+    const int64_t n = std::min<int64_t>(capacity, static_cast<int64_t>(v.size()));
+    std::copy(v.begin(), v.begin() + n, ms);
+    *count = static_cast<int64_t>(v.size());
     return CR_OK;
 }
 

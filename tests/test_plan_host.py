@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "codedreduce.h")) as f:
         header = f.read()
     declared = set(re.findall(r"^(?:int|void|const char \*)\s*\**(cr_\w+)\(", header, flags=re.M))
-    assert declared == set(cr.EXPORTS) and len(declared) == 28
+    assert declared == set(cr.EXPORTS) and len(declared) == 29
     lib = ctypes.CDLL(cr.LIB_PATH)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -285,7 +285,9 @@ def test_argument_errors(plans):
     # timing: the kernel selection is a mask over the five kernel ids
     assert lib.cr_profile_enable(p, cr.CR_PROFILE_ALL + 1) == cr.CR_E_INVAL and lib.cr_profile_enable(p, -1) == cr.CR_E_INVAL
     assert lib.cr_profile_enable(p, 1 << cr.CR_K_ENCODE) == cr.CR_OK and lib.cr_profile_enable(p, 0) == cr.CR_OK
-    assert cr.cr_profile_read(p, cr.CR_K_ENCODE) == (0.0, 0, 0)
+    assert cr.cr_profile_read(p, cr.CR_K_ENCODE) == (0.0, 0, 0) and len(cr.cr_profile_samples(p, cr.CR_K_ENCODE)) == 0
+    import ctypes as _ct
+    assert lib.cr_profile_samples(p, 99, None, 0, _ct.byref(_ct.c_int64())) == cr.CR_E_INVAL
     # the read-bandwidth yardstick checks its arguments before it touches the device
     import ctypes
     gbps = ctypes.c_double()
