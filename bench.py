@@ -3,7 +3,8 @@
 
 One "step" is one pass of the whole path over one batch of synthetic input already resident in HBM:
 host-drawn straggler mask -> cr_partial_grads -> cr_encode_tree -> cr_decode_root -> gradient step
-(issued through cr_gd_run, which enqueues these steps for every mask; the gradient step rides in the decode launch).
+(issued through cr_gd_run -- cr_aggregate_run for the aggregation-only workloads -- which enqueues these steps for every mask,
+the encode programs of 16 steps per host-to-device copy; the gradient step rides in the decode launch).
 
 Prints ONE JSON line.  Its top level is the headline workload (configuration 5: the largest, end-to-end iterations/s);
 "configs" holds the same record for every benchmark configuration and for the comparison workloads of the paper's
@@ -196,14 +197,11 @@ def run_workload(name: str, steps: int, warmup: int, cpu_budget: float, args) ->
     def run(masks):
         # the whole path for every host-drawn straggler mask; for regression workloads the gradient-descent loop is one library
         # call per batch of masks, which enqueues its steps without waiting for the device
-        if aggregate:
-            for mask in masks:
-                cr.cr_load_partial_grads(plan, G_dev)
-                cr.cr_encode_tree(plan, mask)
-                cr.cr_decode_root(plan, g_dev)
-        else:
-            for lo in range(0, len(masks), 8):
-                cr.cr_gd_run(plan, X_dev, y_dev, w_dev, g_dev, masks[lo:lo + 8], lr)
+        for lo in range(0, len(masks), 16):
+            if aggregate:
+                cr.cr_aggregate_run(plan, G_dev, masks[lo:lo + 16], g_dev)
+            else:
+                cr.cr_gd_run(plan, X_dev, y_dev, w_dev, g_dev, masks[lo:lo + 16], lr)
 
     dominant = "encode" if aggregate else "partial_grads"
     dom_id = KERNEL_NAMES.index(dominant)

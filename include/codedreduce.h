@@ -151,7 +151,7 @@ int cr_simulate_iteration(const cr_plan_t *plan, double a, double mu, double t_c
                           uint8_t *mask, double *ready, double *total);
 
 /* ---- device binding --------------------------------------------------------------------------------------------
- * The workspace holds the device tables, the per-call encode program, the stage-1 piece partials, the slab gradients
+ * The workspace holds the device tables, 16 encode programs, the stage-1 piece partials, the slab gradients
  * G[S][d] (not for CR_AGGREGATE_ONLY) and the messages M[N][d], all fp32 rows of d floats.  dev_ptr must be 256-byte aligned and stay valid while the plan
  * is used; hip_stream is a hipStream_t (NULL = the default stream).  cr_bind_workspace copies the tables synchronously. */
 int cr_workspace_bytes(cr_plan_t *plan, size_t *bytes);
@@ -181,7 +181,8 @@ int cr_decode_root(cr_plan_t *plan, float *g_dev);
 int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
 
 /* Gradient descent loop kept on the device (eq. (2) with a plain step): `steps` times  g = CodedReduce(w);  w <- w - lr g,  enqueued
- * back to back with no host synchronisation beyond the staging ring of the encode programs (the host runs at most 4 steps ahead).
+ * back to back.  The encode programs of 16 steps at a time travel to the device in one copy, so a step is kernel launches only; the
+ * host waits only when it runs more than 32 steps ahead of the copies (two pinned staging batches).
  *   masks_host      steps x N bytes, one straggler mask per step; all are checked first: CR_E_UNDECODABLE before anything is enqueued
  *   w_dev, g_dev    d floats each; w is updated in place, g holds the last decoded gradient
  *   w_star_or_null  d floats (device): the reference model of the normalised error rate, or NULL
@@ -190,6 +191,16 @@ int cr_gd_update(cr_plan_t *plan, float *w_dev, const float *g_dev, float lr);
  *                   which then rides in the decode launch (the same arithmetic as cr_gd_update, one launch fewer per step) */
 int cr_gd_run(cr_plan_t *plan, const void *X_dev, const float *y_dev, float *w_dev, float *g_dev, const uint8_t *masks_host,
               int steps, float lr, const float *w_star_or_null, float *metrics_or_null);
+
+/* Aggregation alone, many masks in one call (CR.Execute steps 2 to the end, Algorithm 2, once per mask): step t encodes the slab
+ * gradients at G_dev + t * G_step_stride under masks_host[t] and decodes into g_dev + t * g_step_stride; like cr_load_partial_grads,
+ * cr_encode_tree and cr_decode_root called in turn (the same bits), but with the programs of 16 steps per host-to-device copy.
+ *   G_dev          device, S x d floats per step, 16-byte aligned; G_step_stride in floats (a multiple of 4): 0 = the same slabs every step
+ *   masks_host     steps x N bytes; all are checked first: CR_E_UNDECODABLE before anything is enqueued
+ *   g_dev          device, d floats per step; g_step_stride in floats: 0 = every step overwrites the same vector
+ * Afterwards the plan is in the state the last step's three calls would have left (messages of the last mask). */
+int cr_aggregate_run(cr_plan_t *plan, const float *G_dev, int64_t G_step_stride, const uint8_t *masks_host, int steps, float *g_dev,
+                     int64_t g_step_stride);
 
 /* ---- aggregation without any allocation ----------------------------------------------------------------------------------------
  * For callers that cannot allocate or bind device memory: code under HIP stream capture, tight serving loops, harnesses that forbid

@@ -28,7 +28,7 @@ EXPORTS = [
     "cr_plan_decode_row", "cr_plan_set_split", "cr_plan_get_pieces", "cr_simulate_iteration", "cr_workspace_bytes", "cr_bind_workspace",
     "cr_partial_grads", "cr_load_partial_grads", "cr_encode_tree", "cr_decode_root", "cr_gd_update", "cr_gd_run", "cr_get_slab_grads",
     "cr_get_messages", "cr_profile_enable", "cr_profile_read", "cr_last_algorithmic_bytes", "cr_synchronize", "cr_last_error",
-    "cr_probe_read_bandwidth", "cr_aggregate_static", "cr_profile_samples",
+    "cr_probe_read_bandwidth", "cr_aggregate_static", "cr_profile_samples", "cr_aggregate_run",
 ]
 
 
@@ -81,6 +81,7 @@ def load_library():
         lib.cr_gd_update.argtypes = [vp, vp, vp, ctypes.c_float]
         lib.cr_gd_run.argtypes = [vp, vp, vp, vp, vp, vp, c_int, ctypes.c_float, vp, vp]
         lib.cr_aggregate_static.argtypes = [vp, vp, vp, vp, vp]
+        lib.cr_aggregate_run.argtypes = [vp, vp, i64, vp, c_int, vp, i64]
         lib.cr_get_slab_grads.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_get_messages.argtypes = [vp, ctypes.POINTER(vp)]
         lib.cr_profile_enable.argtypes = [vp, c_int]
@@ -275,6 +276,18 @@ def cr_gd_run(plan: int, X, y, w, g, masks, lr: float, w_star=None, metrics=None
                                     _dev(w, "w", "f32", info.d), _dev(g, "g", "f32", info.d), m.ctypes.data, m.shape[0], lr,
                                     _dev(w_star, "w_star", "f32", info.d, optional=True),
                                     _dev(metrics, "metrics", "f32", 2 * m.shape[0], optional=True)))
+
+
+def cr_aggregate_run(plan: int, G, masks, g, G_step_stride: int = 0, g_step_stride: int = 0) -> None:
+    info = cr_plan_info(plan)
+    m = np.ascontiguousarray(masks, dtype=np.uint8)
+    if m.ndim != 2 or m.shape[1] != info.num_workers:
+        raise ValueError("masks must be steps x N bytes")
+    steps = m.shape[0]
+    need_G = info.num_slabs * info.d + max(0, steps - 1) * G_step_stride
+    need_g = info.d + max(0, steps - 1) * g_step_stride
+    _check(load_library().cr_aggregate_run(plan, _dev(G, "G", "f32", need_G), G_step_stride, m.ctypes.data, steps,
+                                           _dev(g, "g", "f32", need_g), g_step_stride))
 
 
 CR_STATIC_SCRATCH_BYTES = 96 << 20

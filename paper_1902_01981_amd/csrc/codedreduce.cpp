@@ -40,7 +40,8 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 constexpr uint64_t kDefaultSeed = 190201981ull;
-constexpr int kStagingSlots = 4;
+constexpr int kProgramSlots = 16;     // encode programs the workspace holds at once: one host-to-device copy serves that many steps
+constexpr int kStagingHalves = 2;     // pinned staging is two such batches, so the host fills one while the other is being copied
 constexpr size_t kMaxSamples = size_t(1) << 16;
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -84,14 +85,15 @@ struct cr_plan_s {
     int32_t *d_team_piece_begin = nullptr, *d_slab_piece_begin = nullptr, *d_slab_pieces = nullptr;
     int32_t *d_group_item_begin = nullptr, *d_item_pieces = nullptr;   // shared queues only
     uint32_t *d_placement = nullptr;               // kPlacementSlots words: where the workgroups of a probe launch ran
-    char *d_program = nullptr;                     // per-call encode program + root decode terms
-    size_t program_bytes = 0;
+    char *d_program = nullptr;                     // kProgramSlots encode programs (each with its root decode terms)
+    size_t program_bytes = 0;                      // size of one
     float *d_partial = nullptr, *d_G = nullptr, *d_M = nullptr, *d_residuals = nullptr;   // residuals: wide-row path only
     const float *G_src = nullptr;                  // slabs the encode reads: d_G or the caller's buffer
-    char *h_staging = nullptr;                     // pinned, kStagingSlots * program_bytes
-    hipEvent_t staging_done[kStagingSlots] = {};
-    bool staging_used[kStagingSlots] = {};
+    char *h_staging = nullptr;                     // pinned, kStagingHalves * kProgramSlots * program_bytes
+    hipEvent_t staging_done[kStagingHalves] = {};
+    bool staging_used[kStagingHalves] = {};
     int staging_next = 0;
+    int dec_slot = 0;                              // program slot whose decode terms cr_decode_root uses
     // layout of the program block (offsets in bytes, fixed per plan)
     size_t off_slab = 0, off_level = 0, off_row = 0, off_coef = 0, off_acoef = 0, off_sub = 0, off_dec = 0;
     size_t max_terms = 0;
@@ -281,7 +283,7 @@ void compute_layout(cr_plan_t *p, size_t *total)
     w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
     w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
     w = align_up(w + kPlacementSlots * sizeof(uint32_t), 256);
-    w = align_up(w + p->program_bytes, 256);
+    w = align_up(w + kProgramSlots * p->program_bytes, 256);
     const size_t row = static_cast<size_t>(p->d) * sizeof(float);
     if (p->model != CR_AGGREGATE_ONLY) {
         w = align_up(w + P * row, 256);
@@ -587,7 +589,7 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
     p->d_group_item_begin = reinterpret_cast<int32_t *>(p->ws + w);        w = align_up(w + p->split.group_item_begin.size() * sizeof(int32_t), 256);
     p->d_item_pieces = reinterpret_cast<int32_t *>(p->ws + w);             w = align_up(w + p->split.item_pieces.size() * sizeof(int32_t), 256);
     p->d_placement = reinterpret_cast<uint32_t *>(p->ws + w);              w = align_up(w + kPlacementSlots * sizeof(uint32_t), 256);
-    p->d_program = p->ws + w;                                              w = align_up(w + p->program_bytes, 256);
+    p->d_program = p->ws + w;                                              w = align_up(w + kProgramSlots * p->program_bytes, 256);
     p->d_partial = nullptr; p->d_G = nullptr;
     if (p->model != CR_AGGREGATE_ONLY) {
         p->d_partial = reinterpret_cast<float *>(p->ws + w);               w = align_up(w + P * row, 256);
@@ -620,8 +622,8 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
         if (rc != CR_OK) return rc;
     }
     if (!p->h_staging) {
-        CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kStagingSlots, hipHostMallocDefault));
-        for (int i = 0; i < kStagingSlots; ++i) CR_HIP(hipEventCreateWithFlags(&p->staging_done[i], hipEventDisableTiming));
+        CR_HIP(hipHostMalloc(reinterpret_cast<void **>(&p->h_staging), p->program_bytes * kProgramSlots * kStagingHalves, hipHostMallocDefault));
+        for (int i = 0; i < kStagingHalves; ++i) CR_HIP(hipEventCreateWithFlags(&p->staging_done[i], hipEventDisableTiming));
     }
     p->bound = true;
     p->have_grads = false;
@@ -767,39 +769,54 @@ cr::EncProgram program_view(const cr_plan_t *p, const char *d_program)
 
 }  // namespace
 
-int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
+namespace {
+
+// every group of every mask within tolerance?  (checked before anything is enqueued or any staging is touched)
+int check_masks(const cr_plan_t *p, const uint8_t *masks, int steps)
 {
-    if (!p || !mask) return fail(CR_E_INVAL, "NULL argument");
-    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
-    if (!p->have_grads) return fail(CR_E_STATE, "no partial gradients yet");
-    // any group beyond tolerance fails the call before anything is enqueued; checked before a staging slot is taken
-    for (int32_t g = 0; g < p->tree.N / p->n; ++g) {
-        int cnt = 0;
-        for (int j = 0; j < p->n; ++j) cnt += mask[static_cast<size_t>(g) * p->n + j] ? 1 : 0;
-        if (cnt > p->s) return fail(CR_E_UNDECODABLE, "sibling group " + std::to_string(g) + " has more than s stragglers");
+    const int n = p->n;
+    const int32_t N = p->tree.N;
+    for (int t = 0; t < steps; ++t)
+        for (int32_t grp = 0; grp < N / n; ++grp) {
+            int cnt = 0;
+            for (int j = 0; j < n; ++j) cnt += masks[static_cast<size_t>(t) * N + static_cast<size_t>(grp) * n + j] ? 1 : 0;
+            if (cnt > p->s)
+                return fail(CR_E_UNDECODABLE, (steps > 1 ? "step " + std::to_string(t) + ": " : std::string()) + "sibling group " + std::to_string(grp) +
+                                                  " has more than s stragglers");
+        }
+    return CR_OK;
+}
+
+// Builds the encode programs of `count` <= kProgramSlots masks in pinned staging and sends them to program slots 0 .. count-1 with
+// one copy on the plan's stream (which therefore follows every kernel that still reads the slots).  counts[i] describes program i.
+int upload_programs(cr_plan_t *p, const uint8_t *masks, int count, ProgramCounts *counts)
+{
+    const int half = p->staging_next;
+    if (p->staging_used[half]) CR_HIP(hipEventSynchronize(p->staging_done[half]));     // the copy that last read this half is done
+    char *h = p->h_staging + static_cast<size_t>(half) * kProgramSlots * p->program_bytes;
+    for (int i = 0; i < count; ++i) {
+        counts[i] = ProgramCounts();
+        int rc = build_program(p, masks + static_cast<size_t>(i) * p->tree.N, h + static_cast<size_t>(i) * p->program_bytes, &counts[i]);
+        if (rc != CR_OK) return rc;
     }
-    // host staging slot (pinned); wait until the copy that last used it has finished
-    const int slot = p->staging_next;
-    if (p->staging_used[slot]) CR_HIP(hipEventSynchronize(p->staging_done[slot]));
-    char *h = p->h_staging + static_cast<size_t>(slot) * p->program_bytes;
-    ProgramCounts counts;
-    int rc = build_program(p, mask, h, &counts);
-    if (rc != CR_OK) return rc;
-    p->staging_next = (slot + 1) % kStagingSlots;
-    p->num_dec_terms = counts.dec_terms;
+    p->staging_next = (half + 1) % kStagingHalves;
+    CR_HIP(hipMemcpyAsync(p->d_program, h, static_cast<size_t>(count) * p->program_bytes, hipMemcpyHostToDevice, p->stream));
+    CR_HIP(hipEventRecord(p->staging_done[half], p->stream));
+    p->staging_used[half] = true;
+    return CR_OK;
+}
 
-    CR_HIP(hipMemcpyAsync(p->d_program, h, p->program_bytes, hipMemcpyHostToDevice, p->stream));
-    CR_HIP(hipEventRecord(p->staging_done[slot], p->stream));
-    p->staging_used[slot] = true;
-
+int encode_slot(cr_plan_t *p, int slot, const ProgramCounts &counts)
+{
     LaunchTimer t(p, CR_K_ENCODE, (counts.active_slabs + counts.active_msgs) * p->d * 4);
-    CR_HIP(cr::launch_encode(p->G_src, p->d_M, program_view(p, p->d_program), p->n, p->L, p->d, p->stream));
+    CR_HIP(cr::launch_encode(p->G_src, p->d_M, program_view(p, p->d_program + static_cast<size_t>(slot) * p->program_bytes), p->n, p->L, p->d, p->stream));
     t.done();
+    p->num_dec_terms = counts.dec_terms;
+    p->dec_slot = slot;
     p->have_messages = true;
     return CR_OK;
 }
 
-namespace {
 // the master's decode; with w != nullptr the gradient step w <- w - lr g rides in the same launch
 int decode_root(cr_plan_t *p, float *g, float *w, float lr)
 {
@@ -807,12 +824,26 @@ int decode_root(cr_plan_t *p, float *g, float *w, float lr)
     if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
     if (!p->have_messages) return fail(CR_E_STATE, "no messages yet: call cr_encode_tree first");
     LaunchTimer t(p, CR_K_DECODE, static_cast<int64_t>(p->num_dec_terms + 1 + (w ? 2 : 0)) * p->d * 4);
-    CR_HIP(cr::launch_decode(p->d_M, g, reinterpret_cast<const cr::DecTerm *>(p->d_program + p->off_dec), p->num_dec_terms, p->d, w, lr,
-                             p->stream));
+    const char *prog = p->d_program + static_cast<size_t>(p->dec_slot) * p->program_bytes;
+    CR_HIP(cr::launch_decode(p->d_M, g, reinterpret_cast<const cr::DecTerm *>(prog + p->off_dec), p->num_dec_terms, p->d, w, lr, p->stream));
     t.done();
     return CR_OK;
 }
+
 }  // namespace
+
+int cr_encode_tree(cr_plan_t *p, const uint8_t *mask)
+{
+    if (!p || !mask) return fail(CR_E_INVAL, "NULL argument");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (!p->have_grads) return fail(CR_E_STATE, "no partial gradients yet");
+    int rc = check_masks(p, mask, 1);
+    if (rc != CR_OK) return rc;
+    ProgramCounts counts;
+    rc = upload_programs(p, mask, 1, &counts);
+    if (rc != CR_OK) return rc;
+    return encode_slot(p, 0, counts);
+}
 
 int cr_decode_root(cr_plan_t *p, float *g) { return decode_root(p, g, nullptr, 0.f); }
 
@@ -833,25 +864,51 @@ int cr_gd_run(cr_plan_t *p, const void *X, const float *y, float *w, float *g, c
     if (steps < 0) return fail(CR_E_INVAL, "steps must be >= 0");
     if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
     if (p->model == CR_AGGREGATE_ONLY) return fail(CR_E_STATE, "aggregation-only plan has no gradient stage");
-    const int n = p->n;
+    int rc = check_masks(p, masks, steps);              // every mask is checked before anything is enqueued
+    if (rc != CR_OK) return rc;
     const int32_t N = p->tree.N;
-    for (int t = 0; t < steps; ++t)                     // every mask is checked before anything is enqueued
-        for (int32_t grp = 0; grp < N / n; ++grp) {
-            int cnt = 0;
-            for (int j = 0; j < n; ++j) cnt += masks[static_cast<size_t>(t) * N + static_cast<size_t>(grp) * n + j] ? 1 : 0;
-            if (cnt > p->s)
-                return fail(CR_E_UNDECODABLE, "step " + std::to_string(t) + ": sibling group " + std::to_string(grp) + " has more than s stragglers");
-        }
-    for (int t = 0; t < steps; ++t) {
-        int rc = cr_partial_grads(p, X, y, w);
-        if (rc == CR_OK) rc = cr_encode_tree(p, masks + static_cast<size_t>(t) * N);
-        // without the convergence measures the gradient step rides in the decode launch (same arithmetic as cr_gd_update)
-        if (rc == CR_OK) rc = decode_root(p, g, metrics ? nullptr : w, lr);
+    ProgramCounts counts[kProgramSlots];
+    for (int t0 = 0; t0 < steps; t0 += kProgramSlots) {
+        // the programs of the next kProgramSlots steps travel in one copy; the steps themselves are kernel launches only
+        const int count = std::min(kProgramSlots, steps - t0);
+        rc = upload_programs(p, masks + static_cast<size_t>(t0) * N, count, counts);
         if (rc != CR_OK) return rc;
-        if (metrics) {
-            LaunchTimer tm(p, CR_K_UPDATE, 3 * p->d * 4 + (w_star ? p->d * 4 : 0));
-            CR_HIP(cr::launch_update_metrics(w, g, lr, w_star, metrics + 2 * static_cast<size_t>(t), p->d, p->stream));
-            tm.done();
+        for (int i = 0; i < count; ++i) {
+            rc = cr_partial_grads(p, X, y, w);
+            if (rc == CR_OK) rc = encode_slot(p, i, counts[i]);
+            // without the convergence measures the gradient step rides in the decode launch (same arithmetic as cr_gd_update)
+            if (rc == CR_OK) rc = decode_root(p, g, metrics ? nullptr : w, lr);
+            if (rc != CR_OK) return rc;
+            if (metrics) {
+                LaunchTimer tm(p, CR_K_UPDATE, 3 * p->d * 4 + (w_star ? p->d * 4 : 0));
+                CR_HIP(cr::launch_update_metrics(w, g, lr, w_star, metrics + 2 * static_cast<size_t>(t0 + i), p->d, p->stream));
+                tm.done();
+            }
+        }
+    }
+    return CR_OK;
+}
+
+int cr_aggregate_run(cr_plan_t *p, const float *G, int64_t G_step_stride, const uint8_t *masks, int steps, float *g, int64_t g_step_stride)
+{
+    if (!p || !G || !masks || !g) return fail(CR_E_INVAL, "NULL argument");
+    if (steps < 0 || G_step_stride < 0 || g_step_stride < 0) return fail(CR_E_INVAL, "steps and strides must be >= 0");
+    if (!p->bound) return fail(CR_E_INVAL, "no workspace bound");
+    if (reinterpret_cast<uintptr_t>(G) % 16 != 0 || (G_step_stride * sizeof(float)) % 16 != 0) return fail(CR_E_INVAL, "G and its step stride must be 16-byte aligned");
+    int rc = check_masks(p, masks, steps);
+    if (rc != CR_OK) return rc;
+    const int32_t N = p->tree.N;
+    ProgramCounts counts[kProgramSlots];
+    for (int t0 = 0; t0 < steps; t0 += kProgramSlots) {
+        const int count = std::min(kProgramSlots, steps - t0);
+        rc = upload_programs(p, masks + static_cast<size_t>(t0) * N, count, counts);
+        if (rc != CR_OK) return rc;
+        for (int i = 0; i < count; ++i) {
+            p->G_src = G + static_cast<int64_t>(t0 + i) * G_step_stride;
+            p->have_grads = true;
+            rc = encode_slot(p, i, counts[i]);
+            if (rc == CR_OK) rc = decode_root(p, g + static_cast<int64_t>(t0 + i) * g_step_stride, nullptr, 0.f);
+            if (rc != CR_OK) return rc;
         }
     }
     return CR_OK;

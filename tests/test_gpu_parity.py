@@ -339,6 +339,79 @@ def test_aggregation_only_network_sized(s):
     cr.cr_plan_destroy(plan)
 
 
+def test_aggregate_run_matches_the_three_calls():
+    """cr_aggregate_run over 37 masks (three program uploads) against cr_load_partial_grads + cr_encode_tree + cr_decode_root per mask:
+    the same bits, with one set of slab gradients for all steps and with one per step; and a bad mask enqueues nothing."""
+    torch = _torch()
+    L, n, s, d, steps = 2, 12, 5, 1_003, 37
+    m = 156 * 8
+    plan = cr.cr_plan_ex(L, n, s, m, d, model=cr.CR_AGGREGATE_ONLY)
+    ws = cr.Workspace(plan)
+    S = ws.info.num_slabs
+    rng = np.random.default_rng(99)
+    masks = np.stack([wl.draw_mask(rng, L, n, s) for _ in range(steps)])
+    masks[5, ::n] = 0                                    # fewer than s stragglers in every group of one step
+    stride = (S * d + 3) // 4 * 4                        # per-step slab sets, 16-byte aligned
+    G_all = torch.randn(steps * stride, dtype=torch.float32, device="cuda")
+    for per_step in (False, True):
+        g_ref = torch.empty(steps, d, dtype=torch.float32, device="cuda")
+        for t in range(steps):
+            off = t * stride if per_step else 0
+            cr.cr_load_partial_grads(plan, G_all[off:off + S * d])
+            cr.cr_encode_tree(plan, masks[t])
+            cr.cr_decode_root(plan, g_ref[t])
+        M_ref = ws.messages().clone()
+        g_run = torch.full((steps, d), float("nan"), dtype=torch.float32, device="cuda")
+        cr.cr_aggregate_run(plan, G_all, masks, g_run, G_step_stride=stride if per_step else 0, g_step_stride=d)
+        cr.cr_synchronize(plan)
+        assert torch.equal(g_run, g_ref) and torch.equal(ws.messages(), M_ref), per_step
+        if per_step:
+            assert not torch.equal(g_run[0], g_run[1])
+        else:
+            last_same_slabs = g_ref[-1].clone()
+    g_one = torch.empty(d, dtype=torch.float32, device="cuda")
+    cr.cr_aggregate_run(plan, G_all, masks, g_one)       # stride 0: every step overwrites the same vector; the last one stays
+    cr.cr_synchronize(plan)
+    assert torch.equal(g_one, last_same_slabs)
+    before = g_one.clone()
+    bad = masks.copy()
+    bad[20, 0:6] = 1
+    with pytest.raises(cr.CodedReduceError) as ei:
+        cr.cr_aggregate_run(plan, G_all, bad, g_one)
+    assert ei.value.status == cr.CR_E_UNDECODABLE
+    cr.cr_synchronize(plan)
+    assert torch.equal(g_one, before)
+    cr.cr_plan_destroy(plan)
+
+
+def test_gd_run_across_program_batches():
+    """40 steps in one cr_gd_run call (three uploads of encode programs) against the step-by-step calls: bit-identical models and
+    convergence measures; then the same masks in two calls of 23 and 17."""
+    torch = _torch()
+    cfg = wl.config("cfg1")
+    data = wl.make_dataset(cfg)
+    L, n, s = cfg["L"], cfg["n"], cfg["s"]
+    hip = HipPath(L, n, s, data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    steps, lr = 40, 1e-4
+    rng = wl.mask_stream(cfg)
+    masks = np.stack([wl.draw_mask(rng, L, n, s) for _ in range(steps)])
+    w_a = torch.from_numpy(data["w0"]).cuda()
+    for t in range(steps):
+        hip.gradient(w_a, masks[t])
+        cr.cr_gd_update(hip.plan, w_a, hip.g, lr)
+    w_b = torch.from_numpy(data["w0"]).cuda()
+    metrics = torch.zeros(steps, 2, dtype=torch.float32, device="cuda")
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_b, hip.g, masks, lr, None, metrics)
+    w_c = torch.from_numpy(data["w0"]).cuda()
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_c, hip.g, masks[:23], lr)
+    cr.cr_gd_run(hip.plan, hip.X, hip.y, w_c, hip.g, masks[23:], lr)
+    cr.cr_synchronize(hip.plan)
+    assert torch.equal(w_a, w_b) and torch.equal(w_a, w_c)
+    rel = metrics.cpu().numpy()[:, 0]
+    assert np.all(rel > 0) and np.all(metrics.cpu().numpy()[:, 1] == -1)
+    hip.close()
+
+
 LAYERS = [("conv1.weight", 3 * 16 * 3 * 3), ("conv1.bias", 16), ("conv2.weight", 16 * 64 * 4 * 4), ("conv2.bias", 64),
           ("fc1.weight", 64 * 384), ("fc1.bias", 384), ("fc2.weight", 384 * 192), ("fc2.bias", 192), ("fc3.weight", 192 * 10),
           ("fc3.bias", 10)]
