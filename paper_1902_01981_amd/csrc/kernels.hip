@@ -384,15 +384,15 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
                 for (int k = 0; k < K; ++k) xr[r][k] = stage[(cur * R + r) * ROW + tl + k * TS];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                float s = 0.f;
+                float s[4] = {0.f, 0.f, 0.f, 0.f};       // four chains: a sum need not wait for the one before it
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     float xv[VEC];
                     C::widen(__builtin_bit_cast(raw_t, xr[r][k]), xv);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) s = fmaf(xv[v], wv[k][v], s);
+                    for (int v = 0; v < VEC; ++v) s[k & 3] = fmaf(xv[v], wv[k][v], s[k & 3]);
                 }
-                pd[r] = wave_sum<XD == 1>(s);
+                pd[r] = wave_sum<XD == 1>((s[0] + s[1]) + (s[2] + s[3]));
             }
             if constexpr (WAVES > 1) {
                 if ((tl & 63) == 0) {
@@ -610,10 +610,13 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
                 yy = y[row];
 #pragma unroll
                 for (int k = 0; k < K; ++k) xr[k] = ring[slot * nq + (k < K - 1 ? tl + k * TS : qlast)];
-                float s = 0.f;
+                float s = 0.f, s1 = 0.f;
 #pragma unroll
-                for (int k = 0; k < K; ++k) { s = fmaf(xr[k].x, wv[k][0], s); s = fmaf(xr[k].y, wv[k][1], s); s = fmaf(xr[k].z, wv[k][2], s); s = fmaf(xr[k].w, wv[k][3], s); }
-                pd = wave_sum<false>(s);
+                for (int k = 0; k < K; ++k) {
+                    if (k & 1) { s1 = fmaf(xr[k].x, wv[k][0], s1); s1 = fmaf(xr[k].y, wv[k][1], s1); s1 = fmaf(xr[k].z, wv[k][2], s1); s1 = fmaf(xr[k].w, wv[k][3], s1); }
+                    else { s = fmaf(xr[k].x, wv[k][0], s); s = fmaf(xr[k].y, wv[k][1], s); s = fmaf(xr[k].z, wv[k][2], s); s = fmaf(xr[k].w, wv[k][3], s); }
+                }
+                pd = wave_sum<false>(s + s1);
                 if ((tl & 63) == 0) red[(tib * 2 + par) * WAVES + wave] = pd;
             }
             wait_for(std::integral_constant<int, NB - 2>{});      // my part of the next row has landed; the barrier covers the others'
