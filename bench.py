@@ -321,7 +321,7 @@ def run_workload(name: str, steps: int, warmup: int, cpu_budget: float, args) ->
                    "stage1_split": ["equal_ranges", "row_cells", "shared_cells"][info.split_kind] if info.split_kind >= 0 else None,
                    "stage1_split_value": info.split_value, "stage1_team_size": info.stage1_team_size,
                    "stage1_holders_per_workgroup": info.stage1_teams_per_group if info.stage1_staged else 1,
-                   "l2_domains": info.l2_domains, "l2_sharing_checked": info.l2_sharing},
+                   "l2_domains": info.l2_domains, "l2_sharing_checked": info.l2_sharing, "split_signature": signature},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": baseline,
