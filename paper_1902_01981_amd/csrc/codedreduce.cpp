@@ -344,7 +344,7 @@ int fold_timings(cr_plan_t *p)
 
 // The row-cell and shared-cell splits put the holders of a cell on workgroup ids that are congruent modulo the number of L2
 // domains, trusting that the dispatcher deals workgroups to the dies round-robin.  This runs a launch of kPlacementSlots small
-// workgroups that record the die they ran on and checks exactly that; the verdict is reported by cr_plan_info (l2_sharing).
+// workgroups that record the die they ran on and checks exactly that; the outcome is reported by cr_plan_info (l2_sharing).
 // A device that places workgroups differently still computes the same results, only without the shared fetches.
 int check_l2_sharing(cr_plan_t *p)
 {
