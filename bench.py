@@ -274,6 +274,11 @@ def run_workload(name: str, steps: int, warmup: int, cpu_budget: float, args) ->
                         frac=achieved / FP32_VECTOR_PEAK_TFLOPS, traffic=traffic, flops_per_launch=flops,
                         peak_derivation="256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop per multiply-add = 78.6 TFLOP/s; "
                                         "the published 157.3 TFLOP/s counts packed fp32 instructions, which this build does not issue",
+                        # the least this instruction set allows: no instruction multiplies a bf16 operand by an fp32 one, so an
+                        # element costs a widening operation and two multiply-adds = three vector instructions of 4 clocks per
+                        # wavefront; frac_of_issue_floor = that time / the measured time
+                        issue_floor_ms=3.0 * info.row_visits * d / 64.0 * 4.0 / (256 * 4 * 2.4e9) * 1e3,
+                        frac_of_issue_floor=3.0 * info.row_visits * d / 64.0 * 4.0 / (256 * 4 * 2.4e9) / avg_s,
                         hbm_view=hbm)
     else:
         roofline = dict(common, bound="hbm", achieved=traffic_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
