@@ -318,8 +318,9 @@ def run_workload(name: str, steps: int, warmup: int, cpu_budget: float, args) ->
         "clock_ramp_steps": ramp_steps + 4,
         "ms_per_step": elapsed / steps * 1e3,
         "us_per_iteration": elapsed / steps * 1e6,
-        "dtype": "bf16" if cfg["x_dtype"] == wl.BF16 else "f32",
+        "dtype": "f32",          # the arithmetic type: bf16 rows are widened and every product and sum is fp32
         "config": {"workload": f"{name}: {DESCRIPTIONS[name]}", "L": L, "n": n, "s": s, "m": m, "d": d,
+                   "x_storage": "bf16" if cfg["x_dtype"] == wl.BF16 else "f32",
                    "workers": info.num_workers, "slabs": info.num_slabs, "row_visits": info.row_visits,
                    "computation_load": info.r_cr, "rows_per_worker": [info.min_rows, info.max_rows],
                    "stage1_teams": info.num_teams, "stage1_pieces": info.num_pieces, "code_gamma": info.gamma,
