@@ -191,10 +191,10 @@ int ensure_split(cr_plan_t *p)
         kind = CR_SPLIT_EQUAL_RANGES;
         value = static_cast<int64_t>(slots) * (p->variant ? p->variant->teams_per_block() : 1);
     }
-    // small problems (under 128 rows per compute unit and workgroup) do not repay the staged kernel's start-up: row cells below
-    if (kind < 0 && p->variant_staged && p->row_visits / p->variant_staged->teams_per_block() >= 256 * 128) {
+    // small problems (under 16 rows per compute unit and workgroup) do not repay the staged kernel's start-up: row cells below
+    if (kind < 0 && p->variant_staged && p->row_visits / p->variant_staged->teams_per_block() >= 256 * 16) {
         // Rows staged through LDS: one workgroup per compute unit, each with a queue of cells (see split_shared_queues); the
-        // launch lasts as long as the longest queue.  Take the cell height, 64 to 1024 rows in steps of 8, that makes it
+        // launch lasts as long as the longest queue.  Take the cell height, 16 to 1024 rows in steps of 8, that makes it
         // shortest; ties go to the taller cell (fewer partial rows).
         kind = CR_SPLIT_SHARED_CELLS;
         const int tpb = p->variant_staged->teams_per_block();
@@ -203,7 +203,7 @@ int ensure_split(cr_plan_t *p)
         if (p->row_visits / tpb / 64 <= (int64_t(1) << 16)) {       // with longer queues than that the last round no longer matters
             int64_t best = -1;
             cr::Split trial;
-            for (int64_t c = 64; c <= 1024; c += 8) {
+            for (int64_t c = 16; c <= 1024; c += 8) {
                 cr::split_shared_queues(p->slabs, c, domains, tpb, slots / domains, trial);
                 if (best < 0 || trial.makespan <= best) { best = trial.makespan; value = c; }
             }
