@@ -130,8 +130,8 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *                          1537 to 2560 whole chunks (d a multiple of 4) held by 3 or more workers go straight from HBM into LDS
  *                          (no registers on the way in), 3 holders per workgroup.
  * Default (when this is never called): with s = 0 (no row is held twice) equal ranges, one per resident workgroup; else shared
- * cells where that kernel exists and the problem has at least 128 rows per compute unit and workgroup, with the cell height
- * (64 to 1024 rows) that gives the shortest longest queue; else row cells of about 2 MB of X (96 to 512 rows, fewer for
+ * cells where that kernel exists and the problem has at least 16 rows per compute unit and workgroup, with the cell height
+ * (16 to 1024 rows) that gives the shortest longest queue; else row cells of about 2 MB of X (96 to 512 rows, fewer for
  * small problems).  CR_E_STATE once a workspace is bound. */
 enum cr_split { CR_SPLIT_EQUAL_RANGES = 0, CR_SPLIT_ROW_CELLS = 1, CR_SPLIT_SHARED_CELLS = 2 };
 int cr_plan_set_split(cr_plan_t *plan, int kind, int64_t value);
