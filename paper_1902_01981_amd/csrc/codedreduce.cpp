@@ -604,7 +604,9 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
         int64_t visit = 0;
         for (size_t i = 0; i < P; ++i) {
             const int64_t rows = p->split.pieces[i].row_end - p->split.pieces[i].row_begin;
-            hp[i] = {p->split.pieces[i].row_begin, visit, static_cast<int32_t>(rows), p->split.pieces[i].slab};
+            // shared cells know which of them several workgroups fetch; under the other splits a row is fetched by each of its holders
+            const int32_t shared = p->split_kind_used == CR_SPLIT_SHARED_CELLS ? p->split.pieces[i].shared : (p->s > 0 ? 1 : 0);
+            hp[i] = {p->split.pieces[i].row_begin, visit, static_cast<int32_t>(rows), p->split.pieces[i].slab, shared, 0};
             visit += rows;
         }
         CR_HIP(hipMemcpy(p->d_pieces, hp.data(), P * sizeof(cr::DevPiece), hipMemcpyHostToDevice));

@@ -11,6 +11,8 @@ struct DevPiece {            // one stage-1 work item: rows [row_begin, row_begi
     int64_t visit_begin;     // index of the piece's first row among all row visits, piece-major (wide-row path: where its residuals live)
     int32_t nrows;
     int32_t slab;
+    int32_t shared;          // 1: other workgroups fetch these rows at the same time, so the fetch should leave them in the L2
+    int32_t reserved;
 };
 
 // Encode program: a post-order list of terms, stored as parallel arrays so that a wavefront fetches kEncodeUnroll terms with a few

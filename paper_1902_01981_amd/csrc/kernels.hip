@@ -97,7 +97,8 @@ template <int VEC> __device__ __forceinline__ bool chunk_owns(int q, int v, int 
 }
 
 // ---- how a chunk of a row of X is fetched and widened to fp32 -------------------------------------------------
-// load(row, e): the chunk at element e of the row that starts at `row` (a wave-uniform pointer; e differs per lane)
+// load(row, e): the chunk at element e of the row that starts at `row` (a wave-uniform pointer; e differs per lane);
+// load_once: the same for rows nobody else reads, with the non-temporal hint, so that they stream past the caches
 template <int XD, int VEC> struct Chunk;
 template <int XD> __device__ __forceinline__ const void *row_ptr(const void *X, int64_t row, int d)
 {
@@ -108,12 +109,14 @@ template <> struct Chunk<0, 4> {
     using raw_t = f4u;
     using lds_t = f4a;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const f4u *>(static_cast<const char *>(row) + e * 4u); }
+    static __device__ __forceinline__ raw_t load_once(const void *row, unsigned e) { return __builtin_nontemporal_load(reinterpret_cast<const f4u *>(static_cast<const char *>(row) + e * 4u)); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
 };
 template <> struct Chunk<1, 8> {
     using raw_t = u4h;
     using lds_t = u4a;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const u4h *>(static_cast<const char *>(row) + e * 2u); }
+    static __device__ __forceinline__ raw_t load_once(const void *row, unsigned e) { return __builtin_nontemporal_load(reinterpret_cast<const u4h *>(static_cast<const char *>(row) + e * 2u)); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[8])
     {
         v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -125,11 +128,13 @@ template <> struct Chunk<1, 8> {
 template <> struct Chunk<0, 1> {      // rows shorter than one wide chunk
     using raw_t = float;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const float *>(static_cast<const char *>(row) + e * 4u); }
+    static __device__ __forceinline__ raw_t load_once(const void *row, unsigned e) { return __builtin_nontemporal_load(reinterpret_cast<const float *>(static_cast<const char *>(row) + e * 4u)); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = r; }
 };
 template <> struct Chunk<1, 1> {
     using raw_t = uint16_t;
     static __device__ __forceinline__ raw_t load(const void *row, unsigned e) { return *reinterpret_cast<const uint16_t *>(static_cast<const char *>(row) + e * 2u); }
+    static __device__ __forceinline__ raw_t load_once(const void *row, unsigned e) { return __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(static_cast<const char *>(row) + e * 2u)); }
     static __device__ __forceinline__ void widen(const raw_t &r, float (&v)[1]) { v[0] = __uint_as_float(static_cast<uint32_t>(r) << 16); }
 };
 
@@ -227,8 +232,17 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
             for (int r = 0; r < R; ++r) {
                 const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
                 const void *row = row_ptr<XD>(X, pc.row_begin + rr, d);
+                // fp32 rows that other holders read too are left in the L2; bf16 rows always are (that path is bound by the vector
+                // ALUs, and a second copy of its loop costs more than streaming gains)
+                if (XD == 1 || pc.shared) {
 #pragma unroll
-                for (int k = 0; k < K; ++k) xr[r][k] = C::load(row, off[k]);
+                    for (int k = 0; k < K; ++k) xr[r][k] = C::load(row, off[k]);
+                } else {
+                    asm volatile("; rows read once" ::: "memory");   // (the markers keep the two kinds of load from being merged into one)
+#pragma unroll
+                    for (int k = 0; k < K; ++k) xr[r][k] = C::load_once(row, off[k]);
+                    asm volatile("; rows read once" ::: "memory");
+                }
             }
             float pd[R];
             if constexpr (XD == 1 && R % 4 == 0) {
@@ -354,13 +368,21 @@ partial_grads_staged_kernel(const void *__restrict__ X, const float *__restrict_
     }
     float acc[K][VEC];
 
+    // rows that other workgroups fetch as well are left in the L2 for them; rows only this workgroup reads stream past it
     auto fetch = [&](raw_t (&P)[R][LPT], int step) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int rr = min(step * R + r, pc.nrows - 1);
             const void *row = row_ptr<XD>(X, pc.row_begin + rr, d);
+            if (pc.shared) {
 #pragma unroll
-            for (int j = 0; j < LPT; ++j) P[r][j] = C::load(row, goff[j]);
+                for (int j = 0; j < LPT; ++j) P[r][j] = C::load(row, goff[j]);
+            } else {
+                asm volatile("; rows read once" ::: "memory");       // (the markers keep the two kinds of load from being merged into one)
+#pragma unroll
+                for (int j = 0; j < LPT; ++j) P[r][j] = C::load_once(row, goff[j]);
+                asm volatile("; rows read once" ::: "memory");
+            }
         }
     };
     auto park = [&](const raw_t (&P)[R][LPT], int buf) {
@@ -491,6 +513,12 @@ __device__ __forceinline__ void load_to_lds_16(const void *gptr, unsigned lds_of
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_offset) : "memory", "m0");
 }
 // wait until at most N of this wavefront's vector memory loads are in flight (the other counters are left alone)
+// the same with the non-temporal hint: for rows that no other workgroup asks for, which then stream past the caches (a plain
+// read of a large buffer reaches 7.0 TB/s that way on this machine, 6.0 to 6.3 without the hint)
+__device__ __forceinline__ void load_to_lds_16_nt(const void *gptr, unsigned lds_offset)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gptr), "s"(lds_offset) : "memory", "m0");
+}
 template <int N> __device__ __forceinline__ void wait_loads()
 {
     static_assert(N >= 0 && N < 64, "the counter has six bits");
@@ -544,6 +572,7 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
         int item;           // index into the queue; item_end: past the end
         int rows_left;      // rows of the current item not yet passed
         int piece;          // compute cursor: this team's piece of the item (-1: none); fetch cursor: unused
+        int shared;         // fetch cursor: do other workgroups fetch the item's rows too?
         int64_t row;        // current row of X
     };
     auto enter = [&](Cursor &c, bool for_compute) {     // settle on the first item at or after c.item that has pieces
@@ -559,6 +588,7 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
             c.row = pc.row_begin;
             c.rows_left = pc.nrows;
             c.piece = for_compute ? mine : ref;
+            c.shared = pc.shared;
             return;
         }
     };
@@ -566,20 +596,30 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     F.item = C.item = item_begin;
     F.rows_left = C.rows_left = 0;
     F.piece = C.piece = -1;
+    F.shared = C.shared = 1;
     F.row = C.row = 0;
     enter(F, false);
     enter(C, true);
     if (C.item >= item_end) return;                        // nothing queued (the same for the whole workgroup)
 
     // loads of the row under the fetch cursor into ring slot `slot`; then the cursor moves on, staying on its last row once the
-    // queue is exhausted
+    // queue is exhausted.  Rows that other workgroups fetch as well are left in the L2 for them; rows that only this workgroup
+    // reads stream past it.
     auto issue = [&](int slot) {
         const float *row = X + F.row * d;
         const unsigned dst = ring_lds + 16u * static_cast<unsigned>(slot * nq + wgwave * 64);
+        if (F.shared) {
 #pragma unroll
-        for (int j = 0; j < LPT - 1; ++j) load_to_lds_16(row + 4 * (threadIdx.x + j * BT), dst + 16u * (j * BT));
-        if (last_any) {
-            if (last_mine) load_to_lds_16(row + 4 * (threadIdx.x + (LPT - 1) * BT), dst + 16u * ((LPT - 1) * BT));
+            for (int j = 0; j < LPT - 1; ++j) load_to_lds_16(row + 4 * (threadIdx.x + j * BT), dst + 16u * (j * BT));
+            if (last_any) {
+                if (last_mine) load_to_lds_16(row + 4 * (threadIdx.x + (LPT - 1) * BT), dst + 16u * ((LPT - 1) * BT));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < LPT - 1; ++j) load_to_lds_16_nt(row + 4 * (threadIdx.x + j * BT), dst + 16u * (j * BT));
+            if (last_any) {
+                if (last_mine) load_to_lds_16_nt(row + 4 * (threadIdx.x + (LPT - 1) * BT), dst + 16u * ((LPT - 1) * BT));
+            }
         }
         if (F.rows_left > 1) { --F.rows_left; ++F.row; }
         else {
@@ -1167,21 +1207,23 @@ hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nte
 }
 
 // ---- yardstick: a plain streaming read ------------------------------------------------------------------------------------
-// Every thread walks the array with a stride of the whole grid, eight 16-byte loads in flight; nothing but the loads and one add
-// per word.  What this reaches is the practical ceiling for traffic that really comes from HBM.
+// Every workgroup walks one contiguous part of the array, eight non-temporal 16-byte loads in flight per thread; nothing but the
+// loads and one add per word.  What this reaches is the practical ceiling for traffic that really comes from HBM (measured on
+// MI355X: 7.0 to 7.1 TB/s; 6.0 to 6.3 without the non-temporal hint, or with a grid-wide stride instead of contiguous parts).
 __global__ void __launch_bounds__(256) stream_read_kernel(const f4a *__restrict__ src, size_t n16, float *__restrict__ sink)
 {
-    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const size_t begin = per * blockIdx.x, end = begin + per < n16 ? begin + per : n16;
     float s = 0.f;
-    size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
+    size_t i = begin + threadIdx.x;
+    for (; i + 7 * 256 < end; i += 8 * 256) {
         f4a v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += v[u].x + v[u].y + v[u].z + v[u].w;
     }
-    for (; i < n16; i += stride) {
+    for (; i < end; i += 256) {
         const f4a v = __builtin_nontemporal_load(src + i);
         s += v.x + v.y + v.z + v.w;
     }

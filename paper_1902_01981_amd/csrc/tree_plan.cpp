@@ -193,7 +193,7 @@ void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int 
 {
     const std::vector<Unit> units = whole_cell_units(slabs, cell_rows);
     // an item = up to teams_per_group holders of one cell = the work of one workgroup for the length of that cell
-    struct Item { size_t ub, ue; };                          // units [ub, ue)
+    struct Item { size_t ub, ue; bool shared = false; };     // units [ub, ue); shared: the cell has other items too
     struct Cell { std::vector<Item> items; };
     std::vector<Cell> cells;
     size_t widest = 1;
@@ -201,7 +201,7 @@ void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int 
         size_t k = i;
         while (k < units.size() && units[k].cell == units[i].cell) ++k;
         Cell c;
-        for (size_t u = i; u < k; u += teams_per_group) c.items.push_back({u, std::min(k, u + teams_per_group)});
+        for (size_t u = i; u < k; u += teams_per_group) c.items.push_back({u, std::min(k, u + teams_per_group), k - i > static_cast<size_t>(teams_per_group)});
         widest = std::max(widest, c.items.size());
         cells.push_back(std::move(c));
         i = k;
@@ -226,7 +226,7 @@ void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int 
     for (size_t r = 0; r < rounds.size(); ++r) {
         const size_t g = r % gangs, x = g % lanes, k = g / lanes;
         for (size_t j = 0; j < gang; ++j)
-            queue[x + lanes * (k * gang + j)].push_back(j < rounds[r].slot.size() ? rounds[r].slot[j] : Item{0, 0});
+            queue[x + lanes * (k * gang + j)].push_back(j < rounds[r].slot.size() ? rounds[r].slot[j] : Item{0, 0, false});
     }
     size_t groups = groups_all;
     auto empty_queue = [&](const std::vector<Item> &q) { return std::all_of(q.begin(), q.end(), [](const Item &it) { return it.ub == it.ue; }); };
@@ -248,7 +248,7 @@ void split_shared_queues(const std::vector<Slab> &slabs, int64_t cell_rows, int 
                 if (it.ub + t >= it.ue) continue;
                 const Unit &u = units[it.ub + t];
                 piece_of[g][i * teams_per_group + t] = static_cast<int32_t>(out.pieces.size());
-                out.pieces.push_back({u.slab, team, u.row_begin, u.row_end});
+                out.pieces.push_back({u.slab, team, u.row_begin, u.row_end, it.shared ? 1 : 0});
             }
         }
         int64_t busy = 0;

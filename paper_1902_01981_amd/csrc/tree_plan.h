@@ -20,6 +20,7 @@ struct Slab {             // one (worker, segment) pair: owns one d-float partia
 struct Piece {            // a contiguous run of one slab's rows handled by one stage-1 team
     int32_t slab, team;
     int64_t row_begin, row_end;
+    int32_t shared = 0;   // shared cells: 1 if other workgroups fetch the same rows at the same time (the cell has several items)
 };
 
 struct Tree {
