@@ -43,7 +43,8 @@ struct Stage1Variant {
     int xd, vec, team_size, k, rows, tpb;
     bool staged;
     const void *fn[2];               // phi = identity, phi = sigmoid
-    int ring = 0;                    // > 0: rows reach LDS by direct global-to-LDS loads into a ring of `ring` batches of `rows` rows
+    int ring = 0;                    // > 0: rows reach LDS by direct global-to-LDS loads into a ring of `ring` rows
+    int w_in_lds = 0;                // 1: the weights sit in LDS behind the ring (one more row of LDS)
     int block() const { return team_size * tpb; }
     int teams_per_block() const { return tpb; }
     // dynamic LDS the launch needs for rows of d columns (0 for variants that keep rows in registers only)
@@ -55,8 +56,8 @@ constexpr size_t kLdsPerWorkgroup = 160 * 1024;   // gfx950
 // Returns nullptr if (x_dtype, d) is outside what the single-pass register kernels cover.
 const Stage1Variant *select_stage1(int x_dtype, int64_t d);
 // The LDS-staged kernel for rows held by up to max_holders workers each, or nullptr if there is none for this type and width.
-// Rows of 1537 to 2560 whole 16-byte chunks (fp32, d a multiple of 4) held by three or more workers get the kernel that loads
-// straight into LDS, three holders per workgroup.
+// Rows of 1537 to 2558 whole 16-byte chunks (fp32, d a multiple of 4) held by three or more workers get the kernel that loads
+// straight into LDS, three or four holders per workgroup.
 const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_holders);
 // Once per variant and device before the first launch (raises the kernel's dynamic LDS limit where needed).
 hipError_t prepare_stage1(const Stage1Variant &v, int64_t d);

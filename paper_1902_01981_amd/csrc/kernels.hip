@@ -512,20 +512,20 @@ __device__ __forceinline__ void load_to_lds_16(const void *gptr, unsigned lds_of
 {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_offset) : "memory", "m0");
 }
-// wait until at most N of this wavefront's vector memory loads are in flight (the other counters are left alone)
 // the same with the non-temporal hint: for rows that no other workgroup asks for, which then stream past the caches (a plain
 // read of a large buffer reaches 7.0 TB/s that way on this machine, 6.0 to 6.3 without the hint)
 __device__ __forceinline__ void load_to_lds_16_nt(const void *gptr, unsigned lds_offset)
 {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gptr), "s"(lds_offset) : "memory", "m0");
 }
+// wait until at most N of this wavefront's vector memory loads are in flight (the other counters are left alone)
 template <int N> __device__ __forceinline__ void wait_loads()
 {
     static_assert(N >= 0 && N < 64, "the counter has six bits");
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int TS, int K, int H, int NB, bool LOGISTIC>
+template <int TS, int K, int H, int NB, bool WL, bool LOGISTIC>
 __global__ void __launch_bounds__(TS * H)
 partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ y, const float *__restrict__ w,
                          const DevPiece *__restrict__ pieces, const int32_t *__restrict__ group_item_begin,
@@ -537,7 +537,8 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     const float *X = static_cast<const float *>(Xv);
     extern __shared__ __align__(16) unsigned char smem[];
     f4a *ring = reinterpret_cast<f4a *>(smem);                                          // [NB][nq] chunks
-    float *red = reinterpret_cast<float *>(smem + sizeof(f4a) * NB * nq);               // [H][2][WAVES]
+    f4a *wl = ring + NB * nq;                                                           // WL: the weights, [nq] chunks
+    float *red = reinterpret_cast<float *>(smem + sizeof(f4a) * (NB + (WL ? 1 : 0)) * nq);   // [H][2][WAVES]
     const unsigned ring_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char *)smem));
     const int tl = threadIdx.x % TS;
     const int tib = __builtin_amdgcn_readfirstlane(threadIdx.x / TS);
@@ -548,14 +549,25 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
 
     // compute role, as in the kernels above: chunks tl, tl + TS, ... of a row; a chunk index past the row reads the row's last chunk
     // with zero weights (K = ceil(nq / TS), so only a thread's last chunk can lie past the row)
-    float wv[K][4];
+    // WL (1024 threads, so 128 registers each): the weights live in LDS behind the ring and are read per row like the row itself;
+    // only a thread's last chunk, the one that may need masking, keeps its weights in registers (wv[0])
+    constexpr int KW = WL ? 1 : K;
+    float wv[KW][4];
     const int qlast = min(tl + (K - 1) * TS, nq - 1);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
+    for (int k = WL ? K - 1 : 0; k < K; ++k) {
         const int q = k < K - 1 ? tl + k * TS : qlast;
         const f4u t = *reinterpret_cast<const f4u *>(w + 4 * q);
         const bool own = tl + k * TS < nq;
-        wv[k][0] = own ? t.x : 0.f; wv[k][1] = own ? t.y : 0.f; wv[k][2] = own ? t.z : 0.f; wv[k][3] = own ? t.w : 0.f;
+        float(&dst)[4] = wv[WL ? 0 : k];
+        dst[0] = own ? t.x : 0.f; dst[1] = own ? t.y : 0.f; dst[2] = own ? t.z : 0.f; dst[3] = own ? t.w : 0.f;
+    }
+    if constexpr (WL) {
+        for (int q = threadIdx.x; q < nq; q += BT) {
+            const f4u t = *reinterpret_cast<const f4u *>(w + 4 * q);
+            f4a v; v.x = t.x; v.y = t.y; v.z = t.z; v.w = t.w;
+            wl[q] = v;                   // visible to the others after the barrier that follows the first fetches
+        }
     }
     float acc[K][4];
 #pragma unroll
@@ -653,8 +665,11 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
                 float s = 0.f, s1 = 0.f;
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
-                    if (k & 1) { s1 = fmaf(xr[k].x, wv[k][0], s1); s1 = fmaf(xr[k].y, wv[k][1], s1); s1 = fmaf(xr[k].z, wv[k][2], s1); s1 = fmaf(xr[k].w, wv[k][3], s1); }
-                    else { s = fmaf(xr[k].x, wv[k][0], s); s = fmaf(xr[k].y, wv[k][1], s); s = fmaf(xr[k].z, wv[k][2], s); s = fmaf(xr[k].w, wv[k][3], s); }
+                    f4a wk;
+                    if (WL && k < K - 1) wk = wl[tl + k * TS];
+                    else { const float(&r)[4] = wv[WL ? 0 : k]; wk.x = r[0]; wk.y = r[1]; wk.z = r[2]; wk.w = r[3]; }
+                    if (k & 1) { s1 = fmaf(xr[k].x, wk.x, s1); s1 = fmaf(xr[k].y, wk.y, s1); s1 = fmaf(xr[k].z, wk.z, s1); s1 = fmaf(xr[k].w, wk.w, s1); }
+                    else { s = fmaf(xr[k].x, wk.x, s); s = fmaf(xr[k].y, wk.y, s); s = fmaf(xr[k].z, wk.z, s); s = fmaf(xr[k].w, wk.w, s); }
                 }
                 pd = wave_sum<false>(s + s1);
                 if ((tl & 63) == 0) red[(tib * 2 + par) * WAVES + wave] = pd;
@@ -1007,8 +1022,12 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
       reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, true>)}}
 #define CR_D(TS, K, NB, H)                                                                             \
     {0, 4, TS, K, 1, H, true,                                                                          \
-     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false>),                  \
-      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true>)}, NB}
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, false>),           \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, true>)}, NB, 0}
+#define CR_DW(TS, K, NB, H)                                                                            \
+    {0, 4, TS, K, 1, H, true,                                                                          \
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, false>),            \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, true>)}, NB, 1}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 const Stage1Variant kVariants[] = {
     // fp32, chunks of 4 columns (4 registers per chunk)
@@ -1023,8 +1042,11 @@ const Stage1Variant kVariants[] = {
     CR_V(1, 8, 256, 6, 2), CR_V(1, 8, 1024, 2, 2), CR_V(1, 8, 1024, 3, 1),
     // rows shorter than one wide chunk: one column per lane
     CR_V(0, 1, 64, 1, 8), CR_V(1, 1, 64, 1, 8),
-    // fp32 rows of 1537 to 2560 whole 16-byte chunks (up to 40 KB) loaded straight into LDS, ring of four rows: three holders per
-    // workgroup (768 threads).  Listed before the register-staged kernels of two holders that cover the same widths.
+    // fp32 rows of 1537 to 2558 whole 16-byte chunks (up to 40 KB) loaded straight into LDS.  Four holders per workgroup (1024
+    // threads, 128 registers each: the weights move to LDS, behind a ring of three rows) where the holder counts make that fewer
+    // workgroups per row; else three holders per workgroup (768 threads) and a ring of four rows.  Listed before the
+    // register-staged kernels of two holders that cover the same widths.
+    CR_DW(256, 7, 3, 4), CR_DW(256, 8, 3, 4), CR_DW(256, 9, 3, 4), CR_DW(256, 10, 3, 4),
     CR_D(256, 7, 4, 3), CR_D(256, 8, 4, 3), CR_D(256, 9, 4, 3), CR_D(256, 10, 4, 3),
     // fp32 rows staged through LDS by way of registers (any width).  Eight holders per workgroup, one wavefront each, for rows of up to 1024 chunks ...
     CR_S(0, 4, 64, 5, 1, 8), CR_S(0, 4, 64, 6, 1, 8), CR_S(0, 4, 64, 7, 1, 8), CR_S(0, 4, 64, 8, 1, 8), CR_S(0, 4, 64, 9, 1, 8),
@@ -1052,7 +1074,7 @@ size_t Stage1Variant::lds_bytes(int64_t d) const
     if (!staged) return 0;
     if (ring > 0) {        // ring of whole rows, then the partial dot products of the teams' wavefronts
         const size_t nq = static_cast<size_t>((d + vec - 1) / vec);
-        return 16 * static_cast<size_t>(ring) * nq + sizeof(float) * tpb * 2 * (team_size / 64);
+        return 16 * static_cast<size_t>(ring + w_in_lds) * nq + sizeof(float) * tpb * 2 * (team_size / 64);
     }
     const size_t row_chunks = static_cast<size_t>((k + tpb - 1) / tpb) * block();
     return 16 * 2 * rows * row_chunks + sizeof(float) * tpb * 2 * rows * (team_size / 64);
@@ -1082,6 +1104,8 @@ const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_ho
     for (const Stage1Variant &v : kVariants) {
         if (!v.staged || v.xd != x_dtype || v.vec != vec || v.k != (nq + v.team_size - 1) / v.team_size || v.tpb > widest) continue;
         if (v.ring > 0 && (d % vec != 0 || v.lds_bytes(d) > kLdsPerWorkgroup)) continue;
+        // four holders per workgroup (weights in LDS) only where that takes fewer workgroups per row than three do
+        if (v.w_in_lds && (max_holders + 3) / 4 >= (max_holders + 2) / 3) continue;
         return &v;
     }
     return nullptr;
