@@ -1236,8 +1236,8 @@ hipError_t launch_decode(const float *M, float *g, const DecTerm *terms, int nte
 // MI355X: 7.0 to 7.1 TB/s; 6.0 to 6.3 without the non-temporal hint, or with a grid-wide stride instead of contiguous parts).
 __global__ void __launch_bounds__(256) stream_read_kernel(const f4a *__restrict__ src, size_t n16, float *__restrict__ sink)
 {
-    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
-    const size_t begin = per * blockIdx.x, end = begin + per < n16 ? begin + per : n16;
+    const size_t per = ((n16 + gridDim.x - 1) / gridDim.x + 2047) / 2048 * 2048;      // whole unrolled iterations: parts start on 32 KB
+    const size_t begin = per * blockIdx.x < n16 ? per * blockIdx.x : n16, end = begin + per < n16 ? begin + per : n16;
     float s = 0.f;
     size_t i = begin + threadIdx.x;
     for (; i + 7 * 256 < end; i += 8 * 256) {
