@@ -114,6 +114,7 @@ struct cr_plan_s {
 namespace {
 
 int64_t elem_size(const cr_plan_t *p) { return p->x_dtype == CR_BF16 ? 2 : 4; }
+constexpr int64_t kStreamFromBytes = int64_t(1) << 30;      // four times the last-level cache: nothing of X survives an iteration
 
 // decode row for one group under rule "pad with the highest-index survivors"; returns CR_E_UNDECODABLE if more than s flags are set
 int group_decode_row(const cr_plan_t *p, const uint8_t *flags, const double **row)
@@ -605,7 +606,10 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
         for (size_t i = 0; i < P; ++i) {
             const int64_t rows = p->split.pieces[i].row_end - p->split.pieces[i].row_begin;
             // shared cells know which of them several workgroups fetch; under the other splits a row is fetched by each of its holders
-            const int32_t shared = p->split_kind_used == CR_SPLIT_SHARED_CELLS ? p->split.pieces[i].shared : (p->s > 0 ? 1 : 0);
+            // ... and a data matrix of a few hundred megabytes stays in the last-level cache (256 MB on MI355X) from one iteration
+            // to the next if its lines are allowed to: only larger ones are streamed past the caches
+            const bool streams = p->m * p->d * elem_size(p) >= kStreamFromBytes;
+            const int32_t shared = !streams ? 1 : p->split_kind_used == CR_SPLIT_SHARED_CELLS ? p->split.pieces[i].shared : (p->s > 0 ? 1 : 0);
             hp[i] = {p->split.pieces[i].row_begin, visit, static_cast<int32_t>(rows), p->split.pieces[i].slab, shared, 0};
             visit += rows;
         }
