@@ -203,6 +203,34 @@ def test_gradient_coding_twenty_workers_full():
     hip.close()
 
 
+def test_uncoded_twenty_workers_full():
+    """One layer, 20 workers, no redundancy, on configuration 2's data (4 GB): nobody else reads a row, so the register kernel
+    fetches every row with the non-temporal hint (only data sets of 1 GiB and more take that path)."""
+    cfg = wl.config("umw20")
+    data = wl.make_dataset(cfg, threads=16)
+    hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, use_native=True)
+    assert (hip.info.split_kind, hip.info.stage1_staged) == (cr.CR_SPLIT_EQUAL_RANGES, 0) and hip.info.row_visits == cfg["m"]
+    _full_first_step(hip, orc, data["w0"], np.zeros(20, dtype=np.uint8), 1e-4)
+    _, ner = _gd_steps(hip, orc, cfg, data, 3, {0, 2}, 1e-4)
+    assert all(b < a for a, b in zip(ner, ner[1:]))
+    hip.close()
+
+
+@pytest.mark.parametrize("L,n,s,m,d,holders", [(1, 4, 2, 30_000, 10_000, 3), (1, 4, 1, 30_000, 10_000, 2), (1, 6, 2, 70_000, 4_096, 4)])
+def test_streamed_cells_full(L, n, s, m, d, holders):
+    """Data sets of 1.1 to 1.2 GB whose every cell belongs to one workgroup: three holders loaded straight into LDS, two and
+    three holders (one idle team) staged through registers, all fetched with the non-temporal hint."""
+    cfg = wl.config("cfg2", L=L, n=n, s=s, m=m, d=d, lr=3e-7)
+    data = wl.make_dataset(cfg, threads=16)
+    hip = HipPath(L, n, s, data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
+    orc = OraclePath(L, n, s, data["X"], data["y"], cr.CR_LINEAR, use_native=True)
+    assert (hip.info.split_kind, hip.info.stage1_staged, hip.info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, 1, holders)
+    rng = wl.mask_stream(cfg)
+    _full_first_step(hip, orc, data["w0"], wl.draw_mask(rng, L, n, s), 1e-4)
+    hip.close()
+
+
 def test_cfg4_full():
     """Aggregation only: L=2, n=8, s=2 (72 workers), 248 partition-gradient vectors of length 2^24, 20 random masks.  The decoded
     vector is checked on every column under every mask (it is the sum of all atoms whatever the mask); for the first two masks
