@@ -68,6 +68,7 @@ struct cr_plan_s {
     // stage-1 split
     const cr::Stage1Variant *variant = nullptr;        // the stage-1 kernel in use (nullptr: two-pass path for very wide rows)
     const cr::Stage1Variant *variant_regs = nullptr, *variant_staged = nullptr;   // what exists for (x_dtype, d)
+    bool rows_as_buffers = false;    // every row starts on a 4-byte boundary and every piece has fewer than 2^31 bytes
     int split_kind = -1;                            // -1: choose from the device when the workspace is sized
     int64_t split_value = 0;
     int split_kind_used = -1;                       // what ensure_split settled on
@@ -602,7 +603,9 @@ int cr_bind_workspace(cr_plan_t *p, void *dev_ptr, size_t bytes, void *hip_strea
 
     if (P > 0) {
         std::vector<cr::DevPiece> hp(P);
-        int64_t visit = 0;
+        int64_t visit = 0, longest = 0;
+        for (size_t i = 0; i < P; ++i) longest = std::max(longest, p->split.pieces[i].row_end - p->split.pieces[i].row_begin);
+        p->rows_as_buffers = (p->d * elem_size(p)) % 4 == 0 && longest * p->d * elem_size(p) < (int64_t(1) << 31);
         for (size_t i = 0; i < P; ++i) {
             const int64_t rows = p->split.pieces[i].row_end - p->split.pieces[i].row_begin;
             // shared cells know which of them several workgroups fetch; under the other splits a row is fetched by each of its holders
@@ -654,7 +657,7 @@ int cr_partial_grads(cr_plan_t *p, const void *X, const float *y, const float *w
                                                    p->model == CR_LOGISTIC ? 1 : 0, p->stream));
         } else if (p->variant) {
             CR_HIP(cr::launch_partial_grads(*p->variant, X, y, w, p->d_pieces, p->d_team_piece_begin, p->split.teams, p->d_partial, p->d,
-                                            p->model == CR_LOGISTIC ? 1 : 0, p->stream));
+                                            p->model == CR_LOGISTIC ? 1 : 0, p->rows_as_buffers, p->stream));
         } else {
             CR_HIP(cr::launch_residuals(p->x_dtype, X, y, w, p->d_pieces, static_cast<int>(P), p->d_residuals, p->d,
                                         p->model == CR_LOGISTIC ? 1 : 0, p->stream));

@@ -45,6 +45,7 @@ struct Stage1Variant {
     const void *fn[2];               // phi = identity, phi = sigmoid
     int ring = 0;                    // > 0: rows reach LDS by direct global-to-LDS loads into a ring of `ring` rows
     int w_in_lds = 0;                // 1: the weights sit in LDS behind the ring (one more row of LDS)
+    const void *fn_buffers[2] = {nullptr, nullptr};   // the same kernel fetching rows with buffer loads (see launch_partial_grads)
     int block() const { return team_size * tpb; }
     int teams_per_block() const { return tpb; }
     // dynamic LDS the launch needs for rows of d columns (0 for variants that keep rows in registers only)
@@ -62,9 +63,11 @@ const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_ho
 // Once per variant and device before the first launch (raises the kernel's dynamic LDS limit where needed).
 hipError_t prepare_stage1(const Stage1Variant &v, int64_t d);
 
+// rows_as_buffers: every row starts on a 4-byte boundary and every piece has fewer than 2^31 bytes; variants that have a
+// buffer-load twin (bf16 rows, one wavefront per team) then run it
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
-                                hipStream_t stream);
+                                bool rows_as_buffers, hipStream_t stream);
 // Staged variants: workgroup g works through items [group_item_begin[g], group_item_begin[g+1]); item i hands team t of the
 // workgroup the piece item_pieces[i * teams_per_block + t] (or -1); all pieces of an item cover the same rows.
 hipError_t launch_partial_grads_staged(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,

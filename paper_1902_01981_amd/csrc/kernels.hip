@@ -64,7 +64,8 @@ template <bool VIA_LDS> __device__ __forceinline__ float wave_sum(float v)
 // holds the sum over its quad of row l & 3; two rotations inside the row of 16 lanes and two exchanges across rows finish the sums,
 // and lanes 0..3 hold the four totals.  13 vector operations, 2 LDS exchanges and 4 lane reads for four rows, where four single
 // sums take about 44.
-__device__ __forceinline__ void wave_sum4(const float (&s)[4], float (&out)[4])
+// wave_sum4_lanes leaves the totals in the lanes (lane l holds the total of row l & 3); wave_sum4 reads them into scalars.
+__device__ __forceinline__ float wave_sum4_lanes(const float (&s)[4])
 {
     const unsigned lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
     const bool b0 = lane & 1u, b1 = lane & 2u;
@@ -77,6 +78,11 @@ __device__ __forceinline__ void wave_sum4(const float (&s)[4], float (&out)[4])
     u += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(u), 0x128, 0xf, 0xf, false));      // row_ror:8
     u += __shfl_xor(u, 16, 64);
     u += __shfl_xor(u, 32, 64);
+    return u;
+}
+__device__ __forceinline__ void wave_sum4(const float (&s)[4], float (&out)[4])
+{
+    const float u = wave_sum4_lanes(s);
 #pragma unroll
     for (int r = 0; r < 4; ++r) out[r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(u), r));
 }
@@ -185,7 +191,7 @@ template <int VEC> __device__ __forceinline__ void store_row_nt(float *dst, cons
 // works on, so a row is fetched once, used for the dot product x.w, kept in registers, and used again for the rank-1 update
 // acc += (phi(x.w) - y) x.  R rows are in flight per step.  The dot is reduced inside the wavefront and, for teams of several
 // wavefronts, through LDS (double buffered: one barrier per step).  Each piece ends with one d-float store of the accumulators.
-template <int XD, int VEC, int TS, int K, int R, bool LOGISTIC>
+template <int XD, int VEC, int TS, int K, int R, bool LOGISTIC, bool BUF = false>
 __global__ void __launch_bounds__((TS < 256 ? 256 : TS))
 partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, const float *__restrict__ w,
                      const DevPiece *__restrict__ pieces, const int32_t *__restrict__ team_piece_begin, int num_teams,
@@ -216,6 +222,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
         }
     }
 
+    const int lane3 = tl & 3;
     const int pb = team_piece_begin[team], pe = team_piece_begin[team + 1];
     int buf = 0;
     for (int p = pb; p < pe; ++p) {
@@ -226,15 +233,27 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[k][v] = 0.f;
 
+        // BUF (chosen by the host where every row starts on a 4-byte boundary and every piece has fewer than 2^31 bytes): the
+        // piece's rows as a buffer -- base, size in bytes, plain 32-bit words
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(row_ptr<XD>(X, pc.row_begin, d)), 0,
+                                                                                 BUF ? pc.nrows * d * (XD == 1 ? 2 : 4) : 0, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(y + pc.row_begin), 0, BUF ? pc.nrows * 4 : 0, 0x00020000);
         for (int r0 = 0; r0 < pc.nrows; r0 += R) {
             raw_t xr[R][K];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int rr = min(r0 + r, pc.nrows - 1);          // rows past the end re-read the last row; their residual is zeroed
                 const void *row = row_ptr<XD>(X, pc.row_begin + rr, d);
-                // fp32 rows that other holders read too are left in the L2; bf16 rows always are (that path is bound by the vector
-                // ALUs, and a second copy of its loop costs more than streaming gains)
-                if (XD == 1 || pc.shared) {
+                if constexpr (BUF) {
+                    // bf16 rows (bound by vector-ALU issue): a buffer load takes the piece's base and the row's offset as scalars
+                    // and the lane's offset as it is, where a global load costs a 64-bit vector add per load
+                    const unsigned soff = static_cast<unsigned>(rr) * static_cast<unsigned>(d) * (XD == 1 ? 2u : 4u);
+#pragma unroll
+                    for (int k = 0; k < K; ++k)
+                        xr[r][k] = __builtin_bit_cast(raw_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off[k] * (XD == 1 ? 2u : 4u), soff, 0));
+                } else if (XD == 1 || pc.shared) {
+                    // fp32 rows that other holders read too are left in the L2; bf16 rows always are (that path is bound by the
+                    // vector ALUs, and a second copy of its loop costs more than streaming gains)
 #pragma unroll
                     for (int k = 0; k < K; ++k) xr[r][k] = C::load(row, off[k]);
                 } else {
@@ -244,7 +263,7 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
                     asm volatile("; rows read once" ::: "memory");
                 }
             }
-            float pd[R];
+            float pd[R], res_of[R];
             if constexpr (XD == 1 && R % 4 == 0) {
                 // bf16 rows are bound by vector-ALU issue: the cross-lane sums of four rows are taken together
 #pragma unroll
@@ -262,9 +281,20 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
                         }
                         s4[r] = s;
                     }
-                    wave_sum4(s4, t4);
+                    if constexpr (BUF && WAVES == 1) {
+                        // the residuals of the four rows in one go, in the lanes that hold the totals: lane l has the target of row
+                        // l & 3 (one 4-byte buffer load per lane; past the piece's end it returns 0 and the row counts for nothing)
+                        const float u = wave_sum4_lanes(s4);
+                        const float yv = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_y, lane3 * 4, (r0 + r0b) * 4, 0));
+                        const float ph = LOGISTIC ? sigmoid(u) : u;
+                        const float rv = lane3 < pc.nrows - (r0 + r0b) ? ph - yv : 0.f;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) pd[r0b + r] = t4[r];
+                        for (int r = 0; r < 4; ++r) res_of[r0b + r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rv), r));
+                    } else {
+                        wave_sum4(s4, t4);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pd[r0b + r] = t4[r];
+                    }
                 }
             } else {
 #pragma unroll
@@ -299,10 +329,14 @@ partial_grads_kernel(const void *__restrict__ X, const float *__restrict__ y, co
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int rr = r0 + r;
-                const float yy = y[pc.row_begin + min(rr, pc.nrows - 1)];
-                const float z = pd[r];
-                const float ph = LOGISTIC ? sigmoid(z) : z;
-                const float res = (rr < pc.nrows) ? ph - yy : 0.f;
+                float res;
+                if constexpr (BUF && XD == 1 && R % 4 == 0 && WAVES == 1) res = res_of[r];
+                else {
+                    const float yy = y[pc.row_begin + min(rr, pc.nrows - 1)];
+                    const float z = pd[r];
+                    const float ph = LOGISTIC ? sigmoid(z) : z;
+                    res = (rr < pc.nrows) ? ph - yy : 0.f;
+                }
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     float xv[VEC];
@@ -1016,6 +1050,12 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
     {XD, VEC, TS, K, R, (TS < 256 ? 256 / TS : 1), false,                                               \
      {reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, false>),                  \
       reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, true>)}}
+#define CR_VB(XD, VEC, TS, K, R)                                                                        \
+    {XD, VEC, TS, K, R, (TS < 256 ? 256 / TS : 1), false,                                               \
+     {reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, false>),                  \
+      reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, true>)}, 0, 0,            \
+     {reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, false, true>),            \
+      reinterpret_cast<const void *>(&partial_grads_kernel<XD, VEC, TS, K, R, true, true>)}}
 #define CR_S(XD, VEC, TS, K, R, H)                                                                      \
     {XD, VEC, TS, K, R, H, true,                                                                        \
      {reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, false>),        \
@@ -1037,7 +1077,8 @@ const Stage1Variant kVariants[] = {
     CR_V(0, 4, 256, 10, 2), CR_V(0, 4, 256, 11, 2), CR_V(0, 4, 256, 12, 2),
     CR_V(0, 4, 1024, 4, 2), CR_V(0, 4, 1024, 5, 1), CR_V(0, 4, 1024, 6, 1),
     // bf16, chunks of 8 columns: they widen to eight accumulators each, so a thread can hold half as many
-    CR_V(1, 8, 64, 1, 8), CR_V(1, 8, 64, 2, 4), CR_V(1, 8, 64, 3, 4), CR_V(1, 8, 64, 4, 2),
+    // (the one-wavefront teams, bound by vector-ALU issue, also come with buffer loads for rows that start on 4-byte boundaries)
+    CR_VB(1, 8, 64, 1, 8), CR_VB(1, 8, 64, 2, 4), CR_VB(1, 8, 64, 3, 4), CR_VB(1, 8, 64, 4, 2),
     CR_V(1, 8, 256, 2, 4), CR_V(1, 8, 256, 3, 4), CR_V(1, 8, 256, 4, 2), CR_V(1, 8, 256, 5, 2),
     CR_V(1, 8, 256, 6, 2), CR_V(1, 8, 1024, 2, 2), CR_V(1, 8, 1024, 3, 1),
     // rows shorter than one wide chunk: one column per lane
@@ -1123,14 +1164,15 @@ hipError_t prepare_stage1(const Stage1Variant &v, int64_t d)
 
 hipError_t launch_partial_grads(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
                                 const int32_t *team_piece_begin, int num_teams, float *partial, int64_t d, int logistic,
-                                hipStream_t stream)
+                                bool rows_as_buffers, hipStream_t stream)
 {
     int di = static_cast<int>(d);
     int nq = static_cast<int>((d + v.vec - 1) / v.vec);
     void *args[] = {&X, &y, &w, &pieces, &team_piece_begin, &num_teams, &partial, &di, &nq};
     const int tpb = v.teams_per_block();
     dim3 grid((num_teams + tpb - 1) / tpb), block(v.block());
-    return hipLaunchKernel(v.fn[logistic ? 1 : 0], grid, block, args, 0, stream);
+    const void *fn = rows_as_buffers && v.fn_buffers[0] ? v.fn_buffers[logistic ? 1 : 0] : v.fn[logistic ? 1 : 0];
+    return hipLaunchKernel(fn, grid, block, args, 0, stream);
 }
 
 hipError_t launch_partial_grads_staged(const Stage1Variant &v, const void *X, const float *y, const float *w, const DevPiece *pieces,
