@@ -100,6 +100,9 @@ CASES = [
     ("odd-d-bf16", 2, 3, 1, 1_111, 270, cr.CR_LINEAR, cr.CR_BF16, None),
     ("odd-d-cfg2", 2, 4, 1, 2_003, 9_999, cr.CR_LOGISTIC, cr.CR_F32, None),       # rows not 16-byte aligned, 10 chunks per thread
     ("odd-d-bf16-k3", 2, 3, 1, 1_500, 1_027, cr.CR_LINEAR, cr.CR_BF16, None),     # rows on odd 2-byte boundaries, last thread chunk mostly inert
+    ("bf16-k3-buffers", 2, 3, 1, 1_503, 1_536, cr.CR_LOGISTIC, cr.CR_BF16, None),  # buffer loads, three chunks per lane, pieces that end inside a trip of four rows
+    ("bf16-k4-buffers", 3, 3, 2, 2_001, 2_042, cr.CR_LINEAR, cr.CR_BF16, (cr.CR_SPLIT_ROW_CELLS, 7)),   # rows on 4-byte (not 16-byte) boundaries, last chunk moved back, cells of 7 rows
+    ("bf16-k1-buffers", 1, 6, 3, 999, 72, cr.CR_LOGISTIC, cr.CR_BF16, (cr.CR_SPLIT_EQUAL_RANGES, 13)),    # one chunk per lane, most lanes idle, pieces across slab boundaries
     ("d-5", 2, 3, 1, 600, 5, cr.CR_LINEAR, cr.CR_F32, None),                      # two chunks sharing three columns
     ("d-9-bf16", 2, 3, 1, 600, 9, cr.CR_LOGISTIC, cr.CR_BF16, None),              # two chunks sharing seven columns
     ("d-3", 2, 3, 1, 600, 3, cr.CR_LINEAR, cr.CR_F32, None),                      # shorter than one chunk: one column per lane
