@@ -1,8 +1,9 @@
-// HIP kernels of the CodedReduce hot path for gfx950 (64-wide wavefronts).  Everything here is bandwidth bound:
-// plain vector FMAs, 16-byte coalesced loads, no matrix cores.
+// HIP kernels of the CodedReduce hot path for gfx950 (64-wide wavefronts).  Everything here is bandwidth bound (stage 1 on bf16
+// rows: bound by vector-ALU issue): plain vector FMAs, 16-byte coalesced loads, no matrix cores.
 //
 //   partial_grads_kernel   CR.Execute step 1: G_piece = X[b:e]^T (phi(X[b:e] w) - y[b:e]) in ONE pass over the rows
 //   partial_grads_staged_kernel   the same, with the rows fetched once per workgroup into LDS for several holders of those rows
+//   partial_grads_dma_kernel      the same, with the rows loaded from global memory straight into LDS (no registers on the way)
 //   residuals_kernel, xt_residuals_kernel   the same in two passes, for rows too wide for one team's registers
 //   reduce_pieces_kernel   sums the pieces of each slab (fixed order, so results are reproducible bit for bit)
 //   encode_kernel          CR.Execute steps 2-5: every node's message, children folded into parents in registers
