@@ -46,7 +46,8 @@ struct Stage1Variant {
     int ring = 0;                    // > 0: rows reach LDS by direct global-to-LDS loads into a ring of `ring` rows
     int w_in_lds = 0;                // 1: the weights sit in LDS behind the ring (one more row of LDS)
     const void *fn_buffers[2] = {nullptr, nullptr};   // the same kernel fetching rows with buffer loads (see launch_partial_grads)
-    int block() const { return team_size * tpb; }
+    int holders_per_team = 1;        // 2: every team of threads works for two of the tpb holders of an item, one after the other
+    int block() const { return team_size * tpb / holders_per_team; }
     int teams_per_block() const { return tpb; }
     // dynamic LDS the launch needs for rows of d columns (0 for variants that keep rows in registers only)
     size_t lds_bytes(int64_t d) const;

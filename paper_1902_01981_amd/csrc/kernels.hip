@@ -560,7 +560,7 @@ template <int N> __device__ __forceinline__ void wait_loads()
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int TS, int K, int H, int NB, bool WL, bool LOGISTIC>
+template <int TS, int K, int H, int NB, bool WL, int HPT, bool LOGISTIC>
 __global__ void __launch_bounds__(TS * H)
 partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ y, const float *__restrict__ w,
                          const DevPiece *__restrict__ pieces, const int32_t *__restrict__ group_item_begin,
@@ -569,11 +569,13 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     constexpr int BT = TS * H, WAVES = TS / 64, LPT = (K + H - 1) / H;     // LPT loads per thread and row; (LPT - 1) * BT < nq always
     static_assert((NB - 1) * LPT < 64, "the loads in flight per wavefront must fit the hardware counter");
     static_assert(NB >= 2 && WAVES > 1, "a ring of at least two rows; teams of several wavefronts");
+    static_assert(HPT == 1 || (HPT == 2 && WL), "a team that works for two holders keeps two sets of accumulators: the weights must be in LDS");
+    constexpr int SLOTS = H * HPT;                          // holders per workgroup: team t works for holders t * HPT ... of an item
     const float *X = static_cast<const float *>(Xv);
     extern __shared__ __align__(16) unsigned char smem[];
     f4a *ring = reinterpret_cast<f4a *>(smem);                                          // [NB][nq] chunks
     f4a *wl = ring + NB * nq;                                                           // WL: the weights, [nq] chunks
-    float *red = reinterpret_cast<float *>(smem + sizeof(f4a) * (NB + (WL ? 1 : 0)) * nq);   // [H][2][WAVES]
+    float *red = reinterpret_cast<float *>(smem + sizeof(f4a) * (NB + (WL ? 1 : 0)) * nq);   // [SLOTS][2][WAVES]
     const unsigned ring_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char *)smem));
     const int tl = threadIdx.x % TS;
     const int tib = __builtin_amdgcn_readfirstlane(threadIdx.x / TS);
@@ -604,9 +606,11 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
             wl[q] = v;                   // visible to the others after the barrier that follows the first fetches
         }
     }
-    float acc[K][4];
+    float acc[HPT][K][4];
 #pragma unroll
-    for (int k = 0; k < K; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+    for (int h = 0; h < HPT; ++h)
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[h][k][0] = acc[h][k][1] = acc[h][k][2] = acc[h][k][3] = 0.f;
     __builtin_amdgcn_s_waitcnt(0);       // the weights are in: from here on the only vector loads of this wavefront are the ring's
 
     // fetch role: thread t brings chunks t, t + BT, ... of every row.  Only the last of them can lie outside the row, and a whole
@@ -618,23 +622,29 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     struct Cursor {
         int item;           // index into the queue; item_end: past the end
         int rows_left;      // rows of the current item not yet passed
-        int piece;          // compute cursor: this team's piece of the item (-1: none); fetch cursor: unused
+        int piece[HPT];     // compute cursor: this team's pieces of the item (-1: none); fetch cursor: [0] = any piece of the item
         int shared;         // fetch cursor: do other workgroups fetch the item's rows too?
         int64_t row;        // current row of X
     };
     auto enter = [&](Cursor &c, bool for_compute) {     // settle on the first item at or after c.item that has pieces
         for (; c.item < item_end; ++c.item) {
-            int ref = -1, mine = -1;
+            int ref = -1, mine[HPT];
 #pragma unroll
-            for (int t = 0; t < H; ++t) {
-                const int pi = item_pieces[c.item * H + t];
-                if (pi >= 0) { if (ref < 0) ref = pi; if (t == tib) mine = pi; }
+            for (int h = 0; h < HPT; ++h) mine[h] = -1;
+#pragma unroll
+            for (int t = 0; t < SLOTS; ++t) {
+                const int pi = item_pieces[c.item * SLOTS + t];
+                if (pi >= 0) {
+                    if (ref < 0) ref = pi;
+                    if (t / HPT == tib) mine[t % HPT] = pi;
+                }
             }
             if (ref < 0) continue;                          // a gap in the queue
             const DevPiece pc = pieces[ref];                // every piece of an item covers the same rows
             c.row = pc.row_begin;
             c.rows_left = pc.nrows;
-            c.piece = for_compute ? mine : ref;
+#pragma unroll
+            for (int h = 0; h < HPT; ++h) c.piece[h] = for_compute ? mine[h] : ref;
             c.shared = pc.shared;
             return;
         }
@@ -642,7 +652,8 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     Cursor F, C;
     F.item = C.item = item_begin;
     F.rows_left = C.rows_left = 0;
-    F.piece = C.piece = -1;
+#pragma unroll
+    for (int h = 0; h < HPT; ++h) F.piece[h] = C.piece[h] = -1;
     F.shared = C.shared = 1;
     F.row = C.row = 0;
     enter(F, false);
@@ -688,51 +699,64 @@ partial_grads_dma_kernel(const void *__restrict__ Xv, const float *__restrict__ 
     __syncthreads();
     int slot = 0, par = 0;
     while (C.item < item_end) {                            // the items of the queue ...
-        const bool active = C.piece >= 0;
+        bool has[HPT];
+        bool active = false;
+#pragma unroll
+        for (int h = 0; h < HPT; ++h) { has[h] = C.piece[h] >= 0; active = active || has[h]; }
         int64_t row = C.row;
         for (int left = C.rows_left; left > 0; --left, ++row) {         // ... and the rows of an item
-            float pd = 0.f, yy = 0.f;
+            float yy = 0.f;
             f4a xr[K];
             if (active) {
                 yy = y[row];
 #pragma unroll
                 for (int k = 0; k < K; ++k) xr[k] = ring[slot * nq + (k < K - 1 ? tl + k * TS : qlast)];
-                float s = 0.f, s1 = 0.f;
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    f4a wk;
-                    if (WL && k < K - 1) wk = wl[tl + k * TS];
-                    else { const float(&r)[4] = wv[WL ? 0 : k]; wk.x = r[0]; wk.y = r[1]; wk.z = r[2]; wk.w = r[3]; }
-                    if (k & 1) { s1 = fmaf(xr[k].x, wk.x, s1); s1 = fmaf(xr[k].y, wk.y, s1); s1 = fmaf(xr[k].z, wk.z, s1); s1 = fmaf(xr[k].w, wk.w, s1); }
-                    else { s = fmaf(xr[k].x, wk.x, s); s = fmaf(xr[k].y, wk.y, s); s = fmaf(xr[k].z, wk.z, s); s = fmaf(xr[k].w, wk.w, s); }
+                for (int h = 0; h < HPT; ++h) {            // every holder forms its own dot product
+                    if (!has[h]) continue;
+                    float s = 0.f, s1 = 0.f;
+#pragma unroll
+                    for (int k = 0; k < K; ++k) {
+                        f4a wk;
+                        if (WL && k < K - 1) wk = wl[tl + k * TS];
+                        else { const float(&r)[4] = wv[WL ? 0 : k]; wk.x = r[0]; wk.y = r[1]; wk.z = r[2]; wk.w = r[3]; }
+                        if (k & 1) { s1 = fmaf(xr[k].x, wk.x, s1); s1 = fmaf(xr[k].y, wk.y, s1); s1 = fmaf(xr[k].z, wk.z, s1); s1 = fmaf(xr[k].w, wk.w, s1); }
+                        else { s = fmaf(xr[k].x, wk.x, s); s = fmaf(xr[k].y, wk.y, s); s = fmaf(xr[k].z, wk.z, s); s = fmaf(xr[k].w, wk.w, s); }
+                    }
+                    const float pd = wave_sum<false>(s + s1);
+                    if ((tl & 63) == 0) red[((tib * HPT + h) * 2 + par) * WAVES + wave] = pd;
                 }
-                pd = wave_sum<false>(s + s1);
-                if ((tl & 63) == 0) red[(tib * 2 + par) * WAVES + wave] = pd;
             }
             wait_for(std::integral_constant<int, NB - 2>{});      // my part of the next row has landed; the barrier covers the others'
             __syncthreads();
             issue(slot);                                         // every team holds this row in registers: its slot is free
             if (active) {
-                float z = 0.f;
 #pragma unroll
-                for (int i = 0; i < WAVES; ++i) z += red[(tib * 2 + par) * WAVES + i];
-                const float res = (LOGISTIC ? sigmoid(z) : z) - yy;
+                for (int h = 0; h < HPT; ++h) {
+                    if (!has[h]) continue;
+                    float z = 0.f;
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    acc[k][0] = fmaf(res, xr[k].x, acc[k][0]); acc[k][1] = fmaf(res, xr[k].y, acc[k][1]);
-                    acc[k][2] = fmaf(res, xr[k].z, acc[k][2]); acc[k][3] = fmaf(res, xr[k].w, acc[k][3]);
+                    for (int i = 0; i < WAVES; ++i) z += red[((tib * HPT + h) * 2 + par) * WAVES + i];
+                    const float res = (LOGISTIC ? sigmoid(z) : z) - yy;
+#pragma unroll
+                    for (int k = 0; k < K; ++k) {
+                        acc[h][k][0] = fmaf(res, xr[k].x, acc[h][k][0]); acc[h][k][1] = fmaf(res, xr[k].y, acc[h][k][1]);
+                        acc[h][k][2] = fmaf(res, xr[k].z, acc[h][k][2]); acc[h][k][3] = fmaf(res, xr[k].w, acc[h][k][3]);
+                    }
                 }
             }
             slot = slot + 1 == NB ? 0 : slot + 1;
             par ^= 1;
         }
-        if (active) {                                      // the item is done: this team's partial row is complete
-            float *out = partial + static_cast<int64_t>(C.piece) * d;
+#pragma unroll
+        for (int h = 0; h < HPT; ++h) {
+            if (!has[h]) continue;                         // the item is done: this holder's partial row is complete
+            float *out = partial + static_cast<int64_t>(C.piece[h]) * d;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int q = tl + k * TS;
-                if (q < nq) { f4u t; t.x = acc[k][0]; t.y = acc[k][1]; t.z = acc[k][2]; t.w = acc[k][3]; *reinterpret_cast<f4u *>(out + 4 * q) = t; }
-                acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+                if (q < nq) { f4u t; t.x = acc[h][k][0]; t.y = acc[h][k][1]; t.z = acc[h][k][2]; t.w = acc[h][k][3]; *reinterpret_cast<f4u *>(out + 4 * q) = t; }
+                acc[h][k][0] = acc[h][k][1] = acc[h][k][2] = acc[h][k][3] = 0.f;
             }
         }
         ++C.item;
@@ -1063,12 +1087,16 @@ update_metrics_kernel(float *__restrict__ w, const float *__restrict__ g, float 
       reinterpret_cast<const void *>(&partial_grads_staged_kernel<XD, VEC, TS, K, R, H, true>)}}
 #define CR_D(TS, K, NB, H)                                                                             \
     {0, 4, TS, K, 1, H, true,                                                                          \
-     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, false>),           \
-      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, true>)}, NB, 0}
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, 1, false>),           \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, false, 1, true>)}, NB, 0}
+#define CR_DW2(TS, K, NB, H)                                                                           \
+    {0, 4, TS, K, 1, 2 * H, true,                                                                      \
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, 2, false>),         \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, 2, true>)}, NB, 1, {nullptr, nullptr}, 2}
 #define CR_DW(TS, K, NB, H)                                                                            \
     {0, 4, TS, K, 1, H, true,                                                                          \
-     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, false>),            \
-      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, true>)}, NB, 1}
+     {reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, 1, false>),            \
+      reinterpret_cast<const void *>(&partial_grads_dma_kernel<TS, K, H, NB, true, 1, true>)}, NB, 1}
 // one variant per exact chunk count K = ceil(row chunks / team size); R rows in flight chosen so a thread holds about 16-24 chunks
 const Stage1Variant kVariants[] = {
     // fp32, chunks of 4 columns (4 registers per chunk)
@@ -1088,6 +1116,7 @@ const Stage1Variant kVariants[] = {
     // threads, 128 registers each: the weights move to LDS, behind a ring of three rows) where the holder counts make that fewer
     // workgroups per row; else three holders per workgroup (768 threads) and a ring of four rows.  Listed before the
     // register-staged kernels of two holders that cover the same widths.
+    CR_DW2(256, 7, 3, 3), CR_DW2(256, 8, 3, 3), CR_DW2(256, 9, 3, 3), CR_DW2(256, 10, 3, 3),
     CR_DW(256, 7, 3, 4), CR_DW(256, 8, 3, 4), CR_DW(256, 9, 3, 4), CR_DW(256, 10, 3, 4),
     CR_D(256, 7, 4, 3), CR_D(256, 8, 4, 3), CR_D(256, 9, 4, 3), CR_D(256, 10, 4, 3),
     // fp32 rows staged through LDS by way of registers (any width).  Eight holders per workgroup, one wavefront each, for rows of up to 1024 chunks ...
@@ -1147,7 +1176,9 @@ const Stage1Variant *select_stage1_staged(int x_dtype, int64_t d, int64_t max_ho
         if (!v.staged || v.xd != x_dtype || v.vec != vec || v.k != (nq + v.team_size - 1) / v.team_size || v.tpb > widest) continue;
         if (v.ring > 0 && (d % vec != 0 || v.lds_bytes(d) > kLdsPerWorkgroup)) continue;
         // four holders per workgroup (weights in LDS) only where that takes fewer workgroups per row than three do
-        if (v.w_in_lds && (max_holders + 3) / 4 >= (max_holders + 2) / 3) continue;
+        if (v.w_in_lds && v.holders_per_team == 1 && (max_holders + 3) / 4 >= (max_holders + 2) / 3) continue;
+        // three teams that each work for two holders: rows with five or six holders in one workgroup
+        if (v.holders_per_team == 2 && max_holders != 5 && max_holders != 6) continue;
         return &v;
     }
     return nullptr;

@@ -189,13 +189,13 @@ def test_four_holders_two_workgroups_per_unit_full():
 
 
 def test_gradient_coding_twenty_workers_full():
-    """One layer, 20 workers, 4 stragglers tolerated, on configuration 2's data: five holders per row, so two workgroups of three
-    teams per cell (three holders and two), side by side in gangs of two."""
+    """One layer, 20 workers, 4 stragglers tolerated, on configuration 2's data: five holders per row, all in one workgroup of three
+    teams that work for two holders each, so that every row is fetched once and streamed."""
     cfg = wl.config("gc20")
     data = wl.make_dataset(cfg, threads=16)
     hip = HipPath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, cr.CR_F32)
     orc = OraclePath(cfg["L"], cfg["n"], cfg["s"], data["X"], data["y"], cr.CR_LINEAR, use_native=True)
-    assert (hip.info.split_kind, hip.info.stage1_staged, hip.info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, 1, 3)
+    assert (hip.info.split_kind, hip.info.stage1_staged, hip.info.stage1_teams_per_group) == (cr.CR_SPLIT_SHARED_CELLS, 1, 6)
     assert hip.info.row_visits == 5 * cfg["m"]
     _full_first_step(hip, orc, data["w0"], wl.draw_mask(wl.mask_stream(cfg), 1, 20, 4), 1e-4)
     _, ner = _gd_steps(hip, orc, cfg, data, 4, {0, 3}, 1e-4)

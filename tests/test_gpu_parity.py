@@ -125,7 +125,8 @@ CASES = [
     ("direct-4-holders-k8", 2, 3, 1, 2_501, 8_192, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 3)),    # 2048 chunks: no partial wavefront in the fetch; cells shorter than the ring
     ("direct-4-holders-8", 3, 4, 1, 2_400, 6_500, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 20)),      # 8, 4 and 2 holders: cells of two workgroups (kept in the L2) and of one (streamed)
     ("direct-3-holders", 1, 4, 2, 3_001, 10_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 37)),      # three holders per row and workgroup, weights in registers; every row streamed
-    ("direct-3-holders-5", 1, 10, 4, 2_000, 9_000, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 11)),   # five holders: three and two, every row shared by two workgroups
+    ("direct-6-holders-5", 1, 10, 4, 2_000, 9_000, cr.CR_LOGISTIC, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 11)),   # five holders in one workgroup: three teams that work for two holders each, one of them for one
+    ("direct-6-holders-6", 1, 12, 5, 1_800, 7_000, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 5)),      # six holders, seven chunks per thread, cells shorter than the ring
     ("direct-3-holders-k9", 1, 6, 2, 2_000, 8_196, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 1)),      # single-row cells: the ring runs across items; last fetch wavefronts idle
     ("direct-widest", 2, 4, 1, 1_500, 10_232, cr.CR_LINEAR, cr.CR_F32, (cr.CR_SPLIT_SHARED_CELLS, 16)),          # 2558 chunks: the ring and the weights fill LDS to the last byte
     ("direct-default", 2, 4, 1, 70_000, 6_400, cr.CR_LINEAR, cr.CR_F32, None),                                  # large enough for the default split to pick it

@@ -169,7 +169,7 @@ def test_row_cell_split(plans, cell_rows):
 @pytest.mark.parametrize("L,n,s,m,d,per_group", [(2, 4, 1, 10_007, 10_000, 4), (3, 4, 1, 25_201, 4_096, 8), (2, 4, 1, 5_003, 2_052, 4),
                                                   (1, 5, 2, 4_001, 3_001, 4), (2, 3, 1, 1_111, 1_028, 4), (2, 4, 1, 6_007, 9_999, 2),
                                                   (1, 4, 1, 4_003, 10_000, 2), (2, 3, 1, 3_001, 6_148, 4), (1, 6, 2, 4_001, 8_192, 3),
-                                                  (1, 10, 4, 4_001, 10_000, 3), (3, 4, 1, 4_001, 6_500, 4), (2, 4, 1, 4_001, 10_232, 4), (2, 4, 1, 4_001, 10_240, 2)])
+                                                  (1, 10, 4, 4_001, 10_000, 6), (1, 12, 5, 4_001, 8_000, 6), (3, 4, 1, 4_001, 6_500, 4), (2, 4, 1, 4_001, 10_232, 4), (2, 4, 1, 4_001, 10_240, 2)])
 @pytest.mark.parametrize("cell_rows", [1, 7, 50, 10 ** 6])
 def test_shared_cell_split(plans, L, n, s, m, d, per_group, cell_rows):
     """Cells laid between slab boundaries and queued on at most 256 workgroups of per_group teams: the holders of a cell sit in
