@@ -128,7 +128,7 @@ int cr_plan_decode_row(const cr_plan_t *plan, const uint8_t *flags /* host, n */
  *                          arithmetic.  One workgroup per compute unit works through a queue of cells (a team then runs
  *                          several pieces).  fp32 rows of 257 to 3072 16-byte chunks with s > 0 only, else CR_E_INVAL.  Rows of
  *                          1537 to 2558 whole chunks (d a multiple of 4) held by 3 or more workers go straight from HBM into LDS
- *                          (no registers on the way in), 3 or 4 holders per workgroup.  Rows that a single workgroup reads are
+ *                          (no registers on the way in), 3, 4 or 6 holders per workgroup.  Rows that a single workgroup reads are
  *                          fetched with the non-temporal hint (they stream past the caches) when X has 1 GiB or more.
  * Default (when this is never called): with s = 0 (no row is held twice) equal ranges, one per resident workgroup; else shared
  * cells where that kernel exists and the problem has at least 16 rows per compute unit and workgroup, with the cell height
